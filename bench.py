@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark: decode attention over a long KV cache on one MI355X.
+
+A step is one pass of the whole hot path (ta_decode = decode_partial +
+tree_combine) over one batch of synthetic input already resident in HBM.
+Steps rotate over several distinct K/V buffers so that no step finds its
+input in the 256 MB last-level cache.  Prints ONE JSON line.
+
+  value      algorithmic bytes of a step (valid K and V rows once, plus q, out,
+             lse) divided by the measured step time, GB/s
+  roofline   the dominant kernel (decode_partial) alone: algorithmic bytes per
+             launch / average launch time from events on the launch stream,
+             against the 8 TB/s HBM3E peak
+  cpu_baseline  the fp64 CPU oracle on the same bytes, in the same unit
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+LLC_BYTES = 256 << 20      # Infinity Cache
+
+
+def build_workload(name, device, copy):
+    import ta_workloads as W
+    if name == "llama128k":
+        return W.llama128k(device=device, seed_offset=copy)
+    if name == "million":
+        return W.million(device=device)
+    if name == "ragged":
+        return W.ragged(device=device)
+    if name == "combine":
+        return W.combine_stress(device=device)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def algorithmic_bytes(w):
+    """Valid K and V rows once each, plus q in and out + lse out (bf16 out)."""
+    B, Hq, Hkv, d, N = w.shape
+    return w.kv_bytes() + B * Hq * d * w.q.element_size() + B * Hq * (d * 2 + 4)
+
+
+def read_traffic(workload):
+    """HBM bytes per decode_partial launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 4 and f[0] == workload and f[1] == "decode_partial":
+            return {"fetch_bytes": float(f[2]), "write_bytes": float(f[3])}
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2408_04093_amd as ta
+
+    if not os.path.exists(ta.lib_path()):
+        from paper_2408_04093_amd import build as hip_build
+        hip_build.build()
+    ta.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # distinct input copies so that consecutive steps never hit the last-level cache
+    w0 = build_workload(args.workload, dev, 0)
+    kv = w0.K.numel() * w0.K.element_size() * 2
+    n_copies = 1 if kv >= 8 * LLC_BYTES else max(2, -(-8 * LLC_BYTES // kv))
+    ws = [w0] + [build_workload(args.workload, dev, c) for c in range(1, n_copies)]
+    B, Hq, Hkv, d, N = w0.shape
+    alg = algorithmic_bytes(w0)
+
+    probs = [ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_BF16) for w in ws]
+    P = ta.ta_suggest_chunks(probs[0])
+    wbytes = ta.ta_workspace_bytes(probs[0], P)
+    workspace = torch.empty(wbytes, dtype=torch.uint8, device=dev)
+    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        w, p = ws[i % n_copies], probs[i % n_copies]
+        rc = ta.ta_decode(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), workspace.data_ptr(), wbytes,
+                          out.data_ptr(), lse.data_ptr(), stream)
+        if rc:
+            raise ta.TAError(rc, "ta_decode")
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gbps = alg / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel alone, same launch shape (same P), events on the launch stream
+    bhp = B * Hq * P
+    part_o = workspace[:bhp * d * 4].view(torch.float32)
+    part_m = workspace[bhp * d * 4:bhp * (d + 1) * 4].view(torch.float32)
+    part_l = workspace[bhp * (d + 1) * 4:bhp * (d + 2) * 4].view(torch.float32)
+
+    def partial_only(i):
+        w, p = ws[i % n_copies], probs[i % n_copies]
+        rc = ta.ta_decode_partial(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), P, None,
+                                  part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(), stream)
+        if rc:
+            raise ta.TAError(rc, "ta_decode_partial")
+
+    for i in range(max(2, args.warmup // 4)):
+        partial_only(i)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for i in range(args.steps):
+        partial_only(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    us_partial = ev0.elapsed_time(ev1) * 1e3 / args.steps
+    ach = alg / (us_partial * 1e-6) / 1e9
+    tr = read_traffic(args.workload)
+
+    result = {
+        "metric": "decode_attention_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w0.q.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
+                   "chunks_P": P, "kv_buffers_rotated": n_copies,
+                   "algorithmic_bytes_per_step": alg},
+        "roofline": {"kernel": "decode_partial", "bound": "hbm", "achieved": round(ach, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
+                     "us_per_launch": round(us_partial, 2),
+                     "traffic": tr},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        w = ws[(args.steps - 1) % n_copies]          # the inputs of the last timed step
+        q_c, K_c, V_c = w.q.cpu(), w.K.cpu(), w.V.cpu()
+        vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
+        # bounded sample: whole workload if it is <= ~2 G multiply-adds, else a prefix of the heads
+        macs = 2.0 * Hq * d * (float(w.valid_len.sum()) if w.valid_len is not None else B * N)
+        hq_s = Hq if macs <= 2.5e10 else max(Hq // Hkv, int(Hq * 2.5e10 / macs) // (Hq // Hkv) * (Hq // Hkv))
+        hk_s = hq_s // (Hq // Hkv)
+        nthreads = oracle.max_threads()
+        t0 = time.perf_counter()
+        ref_out, ref_lse = oracle.decode(q_c[:, :hq_s].contiguous(), K_c[:, :hk_s].contiguous(),
+                                         V_c[:, :hk_s].contiguous(), w.scale, vl, nthreads)
+        dt = time.perf_counter() - t0
+        sample_bytes = w.kv_bytes() * hk_s / Hkv
+        got = out[:, :hq_s].float().cpu().numpy().astype(np.float64)
+        rel = float((np.linalg.norm(got - ref_out, axis=-1) /
+                     np.maximum(np.linalg.norm(ref_out, axis=-1), 1e-300)).max())
+        dl = float(np.abs(lse[:, :hq_s].cpu().numpy() - ref_lse).max())
+        result["cpu_baseline"] = {
+            "value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"query heads 0..{hq_s - 1} of {Hq} (kv heads 0..{hk_s - 1}), all keys, one pass"}
+        result["parity_vs_oracle"] = {"rel_l2_bf16_out": rel, "lse_abs": dl}
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,149 @@
+/*
+ * tree_attn.h -- C ABI of the MI355X (gfx950) decode-attention library.
+ *
+ * Exact single-token ("decode") attention over a long KV cache, computed the
+ * way Tree Attention (arXiv 2408.04093) lays it out: the sequence axis is cut
+ * into P chunks, every chunk yields partial softmax statistics (m, l, o), and
+ * the partials are merged with the associative max/logsumexp reduction of
+ * Section 5.1.  In the paper the chunks live on different GPUs and the merge
+ * is three all-reduces (Algorithm 3); here the chunks are workgroups of one
+ * GPU and the merge is a kernel.
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is a DEVICE pointer unless it says "host".  The
+ *     ta_problem struct itself is read on the host.
+ *   - The caller owns all buffers.  The library never allocates, frees,
+ *     copies to the host or synchronises: work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns at once.  Buffers must stay alive until that work has finished.
+ *   - Errors are return codes.  All argument checks run on the host before
+ *     anything is launched; a failed check launches nothing.
+ *   - Scores are s_a = scale * (q . k_a).  scale = 1 is the paper's softmax
+ *     (Section 3); the paper has no scale.
+ *   - Grouped queries: g = Hq / Hkv, query head h reads KV head h / g (integer
+ *     division).  The paper treats heads as independent (Appendix C.1); the
+ *     grouping only changes which K/V a head reads.  All g heads of a group
+ *     are processed by the same workgroup so that K/V bytes are fetched once.
+ *   - Keys at positions >= valid_len[b] do not exist and are never read.
+ *   - lse is the natural-log logsumexp of the scaled scores over the valid
+ *     keys, i.e. the energy F(0) of Observation 1; out is dF/dzeta at 0.
+ *     A sequence with no valid key gives out = 0 and lse = -inf (never NaN).
+ *   - Partials (Algorithm 3, step 2, kept unnormalised):
+ *        m = max_a s_a,  l = sum_a exp(s_a - m),  o = sum_a exp(s_a - m) v_a
+ *     over the keys of one chunk, all fp32:  part_m, part_l [B,Hq,P] and
+ *     part_o [B,Hq,P,d], contiguous.  The paper's per-device (o, lse) are
+ *     o / l and m + log l.  An empty chunk stores (-inf, 0, 0).
+ *   - NaN or Inf in q, K or V: behaviour undefined.
+ */
+#ifndef TREE_ATTN_H
+#define TREE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TA_OK = 0,
+    TA_ERR_NULL = 1,        /* a required pointer is NULL                            */
+    TA_ERR_SHAPE = 2,       /* B, Hq, Hkv, d, N, P or a stride is out of range       */
+    TA_ERR_DTYPE = 3,       /* unknown ta_dtype                                      */
+    TA_ERR_ALIGN = 4,       /* a pointer or a row stride is not 16-byte aligned      */
+    TA_ERR_WORKSPACE = 5,   /* workspace smaller than ta_workspace_bytes()           */
+    TA_ERR_UNSUPPORTED = 6, /* valid in principle, not built (e.g. d not in {64,128})*/
+    TA_ERR_HIP = 7          /* the HIP runtime refused the launch                    */
+} ta_status;
+
+typedef enum { TA_BF16 = 0, TA_F32 = 1 } ta_dtype;
+
+/*
+ * One decode-attention problem.  Read on the host only.
+ *   q   [B,Hq,d]       contiguous
+ *   K,V [B,Hkv,N,d]    innermost stride 1; the other strides are given in
+ *                      ELEMENTS and must keep every row 16-byte aligned
+ *                      (stride_n >= d).  A whole [N,d] head slice must span
+ *                      less than 4 GiB.
+ *   d in {64, 128};  Hq % Hkv == 0;  1 <= Hq / Hkv <= 16.
+ * bf16 inputs: scores and all sums are accumulated in fp32.
+ * fp32 inputs: scores and the running max are accumulated in fp64, the
+ *              exponentials and sums in fp32.
+ */
+typedef struct ta_problem {
+    int32_t B, Hq, Hkv, d;
+    int64_t N;                                   /* key capacity of K and V            */
+    int64_t k_stride_b, k_stride_h, k_stride_n;  /* elements                           */
+    int64_t v_stride_b, v_stride_h, v_stride_n;  /* elements                           */
+    int32_t qkv_dtype;                           /* ta_dtype shared by q, K and V      */
+    int32_t out_dtype;                           /* ta_dtype of `out` (ta_decode only) */
+    float scale;                                 /* finite; multiplies q . k           */
+    const int32_t *valid_len;                    /* device int32 [B], or NULL = N      */
+} ta_problem;
+
+/* Human-readable name of a status code; never NULL; static storage. */
+const char *ta_status_string(ta_status s);
+
+/*
+ * Chunk count P that ta_decode uses for this problem on the current device
+ * (host-only heuristic: enough workgroups to fill every compute unit several
+ * times over, chunks no shorter than a few hundred keys).  Returns 0 if the
+ * problem is invalid.
+ */
+int32_t ta_suggest_chunks(const ta_problem *p);
+
+/*
+ * Bytes of workspace ta_decode needs when it runs with P chunks:
+ * B*Hq*P*(d+2) floats, rounded up to 256 bytes.  Returns 0 if the problem
+ * is invalid or P < 1.
+ */
+size_t ta_workspace_bytes(const ta_problem *p, int32_t P);
+
+/*
+ * Algorithm 3, steps 1-2: split the keys of every sequence into P chunks and
+ * reduce each chunk to its partial (m, l, o) for every query head.
+ *   chunk_bounds  device int64 [P+1], non-decreasing, shared by every (b, h);
+ *                 chunk j holds keys [bounds[j], bounds[j+1]) intersected with
+ *                 [0, valid_len[b]).  Values are clamped on the device, so a
+ *                 bad table can give wrong chunks but no out-of-range access.
+ *                 NULL = P equal chunks of t = ceil(N / P) keys (the paper's
+ *                 t = N / p), chunk j = [j t, (j+1) t).
+ *   part_m/l/o    outputs, layout above.  Fully overwritten.
+ * One launch; every K and V row of a valid chunk is read exactly once.
+ */
+ta_status ta_decode_partial(const ta_problem *p, const void *q, const void *K, const void *V,
+                            int32_t P, const int64_t *chunk_bounds,
+                            float *part_m, float *part_l, float *part_o, void *stream);
+
+/*
+ * Algorithm 3, steps 3-6 (the arithmetic of the three all-reduces and the
+ * final division), as one P-ary reduction per (b, h) -- Appendix B allows any
+ * fan-in:
+ *     m* = max_j m_j,  w_j = exp(m_j - m*),
+ *     l* = sum_j w_j l_j,  o* = sum_j w_j o_j,
+ *     out = o* / l*,   lse = m* + log l*.
+ * Partials with l_j = 0 are ignored; if all are, out = 0 and lse = -inf.
+ *   part_*   inputs, layout above (d in {64,128}, P >= 1)
+ *   out      [B,Hq,d] of out_dtype (bf16 is rounded to nearest even)
+ *   lse      fp32 [B,Hq]
+ */
+ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
+                          const float *part_m, const float *part_l, const float *part_o,
+                          void *out, int32_t out_dtype, float *lse, void *stream);
+
+/*
+ * The whole path: ta_decode_partial with P = ta_suggest_chunks(p) equal
+ * chunks into `workspace`, then ta_tree_combine.
+ *   workspace        device scratch, 256-byte aligned, at least
+ *                    ta_workspace_bytes(p, ta_suggest_chunks(p)) bytes;
+ *                    contents undefined before and after.
+ *   out [B,Hq,d] (p->out_dtype), lse fp32 [B,Hq].
+ */
+ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const void *V,
+                    void *workspace, size_t workspace_bytes,
+                    void *out, float *lse, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TREE_ATTN_H */

@@ -1,0 +1,386 @@
+// decode_partial: per-chunk partial softmax statistics (m, l, o) for one query
+// token, all heads of a GQA group at once.  Tree Attention (arXiv 2408.04093)
+// Algorithm 3 steps 1-2 with the chunks mapped to workgroups of one gfx950 GPU
+// instead of devices; inside a chunk it is the running-max form of the
+// Section 3 recurrence (n_i = n_{i-1} + v_i s_i, d_i = d_{i-1} + s_i) made safe
+// by the max shift of Appendix F.
+//
+// Data movement (the whole cost: the kernel is HBM-bound)
+//   * A K or V row is D elements = 128..512 bytes.  LPR = row_bytes/16 lanes
+//     each fetch 16 bytes of it with one 128-bit buffer load, so a wave-wide
+//     load covers RPW = 64/LPR complete rows, fully coalesced.
+//   * Every lane therefore owns EPL = 8 (bf16) or 4 (fp32) fixed columns of
+//     the head dimension and one of RPW interleaved "row groups" of keys.
+//     Each row group runs its own online softmax; they are merged at the end.
+//   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
+//     while it computes the current one (register double buffering), so with
+//     8-16 resident waves a CU has tens of KB outstanding.
+//   * All GT query heads that share the KV head are scored against the same
+//     registers: every K/V byte is fetched once per group.
+//
+// Arithmetic
+//   bf16: q.k with v_dot2_f32_bf16 (fp32 accumulate), everything else fp32.
+//   fp32: q.k and the running max in fp64 (full rate on gfx950) so that large
+//         |score| does not cost precision; exponentials and sums in fp32.
+//   Scores are kept in log2 units (score * scale * log2 e) so the exponential
+//   is the bare v_exp_f32; the partial is converted to natural units on store.
+#include "ta_internal.hpp"
+#include "wave_ops.hpp"
+
+namespace ta {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+
+template <int DT> struct Elem;
+template <> struct Elem<TA_BF16> {
+    static constexpr int kBytes = 2;
+    using acc_t = float;    // score / running-max type
+    using q_t = uint32_t;   // one register = two bf16 of q
+};
+template <> struct Elem<TA_F32> {
+    static constexpr int kBytes = 4;
+    using acc_t = double;
+    using q_t = double;     // q widened once
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+    // raw buffer (stride 0): hardware returns 0 for any access past `bytes`
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
+// partial dot product of this lane's 16 bytes of a key row with q
+__device__ __forceinline__ float lane_dot(const v4i &k, const uint32_t (&q)[4]) {
+    float acc = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k[r]),
+                                              __builtin_bit_cast(bf16x2, q[r]), acc, false);
+    return acc;
+}
+__device__ __forceinline__ double lane_dot(const v4i &k, const double (&q)[4]) {
+    double acc = 0.0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc = fma((double)__int_as_float(k[r]), q[r], acc);
+    return acc;
+}
+
+template <int DT, int EPL>
+__device__ __forceinline__ void widen_row(const v4i &v, float (&f)[EPL]) {
+    if constexpr (DT == TA_BF16) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            f[2 * r] = __uint_as_float((uint32_t)v[r] << 16);
+            f[2 * r + 1] = __uint_as_float((uint32_t)v[r] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) f[r] = __int_as_float(v[r]);
+    }
+}
+
+template <int U>
+struct Tile {
+    v4i k[U];
+    v4i v[U];
+};
+
+template <typename acc_t, int GT, int EPL>
+struct State {
+    acc_t m[GT];        // running max, log2 units
+    float l[GT];        // running normaliser
+    float o[GT][EPL];   // running numerator, this lane's columns
+};
+
+template <typename acc_t> __device__ __forceinline__ acc_t neg_inf();
+template <> __device__ __forceinline__ float neg_inf<float>() { return -__builtin_huge_valf(); }
+template <> __device__ __forceinline__ double neg_inf<double>() { return -__builtin_huge_val(); }
+
+// One pipeline step: U keys per row group, GT heads.
+//   row0: chunk-relative index of this lane's first key (u = 0); key u is
+//   row0 + u*RPW.  MASKED steps treat rows >= n as absent.
+template <int DT, int D, int GT, int U, bool MASKED>
+__device__ __forceinline__ void step(const Tile<U> &T, const typename Elem<DT>::q_t (&q)[GT][4],
+                                     State<typename Elem<DT>::acc_t, GT, 16 / Elem<DT>::kBytes> &st,
+                                     typename Elem<DT>::acc_t c, int row0, int n) {
+    using acc_t = typename Elem<DT>::acc_t;
+    constexpr int EPL = 16 / Elem<DT>::kBytes, LPR = D / EPL, RPW = kWave / LPR;
+
+    acc_t s2[U][GT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            acc_t acc = group_sum<LPR>(lane_dot(T.k[u], q[h]));
+            s2[u][h] = acc * c;
+            if constexpr (MASKED)
+                if (row0 + u * RPW >= n) s2[u][h] = neg_inf<acc_t>();
+        }
+    }
+
+    // Raise the running max only when some lane of the wave needs it; once the
+    // stream is warm this is rare and the rescale of o is skipped.
+    acc_t mt[GT];
+    bool need = false;
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        mt[h] = s2[0][h];
+#pragma unroll
+        for (int u = 1; u < U; ++u) mt[h] = fmax(mt[h], s2[u][h]);
+        need |= mt[h] > st.m[h];
+    }
+    if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            const bool up = mt[h] > st.m[h];
+            const float alpha = up ? exp2_hw((float)(st.m[h] - mt[h])) : 1.0f;
+            st.m[h] = up ? mt[h] : st.m[h];
+            st.l[h] *= alpha;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) st.o[h][e] *= alpha;
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float vf[EPL];
+        widen_row<DT, EPL>(T.v[u], vf);
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            float p = exp2_hw((float)(s2[u][h] - st.m[h]));
+            if constexpr (MASKED)
+                if (row0 + u * RPW >= n) p = 0.f;
+            st.l[h] += p;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) st.o[h][e] = fmaf(p, vf[e], st.o[h][e]);
+        }
+    }
+}
+
+template <int DT, int D, int GT, int U>
+__global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
+    using E = Elem<DT>;
+    using acc_t = typename E::acc_t;
+    using q_t = typename E::q_t;
+    constexpr int EPL = 16 / E::kBytes, LPR = D / EPL, RPW = kWave / LPR;
+    constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane % LPR, rg = lane / LPR;
+
+    // workgroup -> (batch, kv head, head slice, chunk); chunk varies fastest
+    uint32_t id = blockIdx.x;
+    const int chunk = id % (uint32_t)a.P;  id /= (uint32_t)a.P;
+    const int slice = id % (uint32_t)a.slices;  id /= (uint32_t)a.slices;
+    const int hk = id % (uint32_t)a.Hkv;
+    const int b = id / (uint32_t)a.Hkv;
+    const int hq0 = hk * a.g + slice * GT;
+
+    int64_t L = a.N;
+    if (a.valid_len) {
+        L = a.valid_len[b];
+        L = L < 0 ? 0 : (L > a.N ? a.N : L);
+    }
+    int64_t lo, hi;
+    if (a.bounds) {
+        lo = a.bounds[chunk];
+        hi = a.bounds[chunk + 1];
+        lo = lo < 0 ? 0 : (lo > L ? L : lo);
+        hi = hi < lo ? lo : (hi > L ? L : hi);
+    } else {
+        lo = (int64_t)chunk * a.t;
+        lo = lo > L ? L : lo;
+        hi = lo + a.t;
+        hi = hi > L ? L : hi;
+    }
+    const int n = (int)(hi - lo);
+
+    const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
+    if (n <= 0) {   // empty chunk: the identity of the merge
+        for (int i = tid; i < GT * D; i += kThreads)
+            a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
+        if (tid < GT) {
+            a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
+            a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+        }
+        return;
+    }
+
+    // q: this lane's EPL columns of each head, kept in registers
+    q_t q[GT][4];
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + sub * EPL) * E::kBytes;
+        const v4i raw = *reinterpret_cast<const v4i *>(qp);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if constexpr (DT == TA_BF16) q[h][r] = (uint32_t)raw[r];
+            else q[h][r] = (double)__int_as_float(raw[r]);
+        }
+    }
+
+    const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * E::kBytes +
+                     lo * (int64_t)a.k_row_bytes;
+    const char *vb = (const char *)a.V + ((int64_t)b * a.v_sb + (int64_t)hk * a.v_sh) * E::kBytes +
+                     lo * (int64_t)a.v_row_bytes;
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kb, (uint32_t)(n - 1) * a.k_row_bytes + D * E::kBytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vb, (uint32_t)(n - 1) * a.v_row_bytes + D * E::kBytes);
+
+    const int n_iters = (n + ROWS_ITER - 1) / ROWS_ITER;
+    const int n_full = n / ROWS_ITER;
+    const int row_lane = w * ROWS_WAVE + rg;   // + it*ROWS_ITER + u*RPW
+
+    uint32_t koff[U], voff[U];   // byte offsets of this lane's loads in iteration 0
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        koff[u] = (uint32_t)(row_lane + u * RPW) * a.k_row_bytes + sub * 16;
+        voff[u] = (uint32_t)(row_lane + u * RPW) * a.v_row_bytes + sub * 16;
+    }
+
+    auto issue = [&](Tile<U> &T, int it) {
+        if (it < n_full) {
+            const uint32_t kinc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
+            const uint32_t vinc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, 0);
+        } else {
+            // ragged last step: rows past the chunk are redirected to its last
+            // row (always in range) and masked out of the arithmetic
+            uint32_t rc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int r = it * ROWS_ITER + row_lane + u * RPW;
+                rc[u] = (uint32_t)(r < n ? r : n - 1);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, 0);
+        }
+    };
+
+    State<acc_t, GT, EPL> st;
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        st.m[h] = neg_inf<acc_t>();
+        st.l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) st.o[h][e] = 0.f;
+    }
+    const acc_t c = (acc_t)a.c;
+
+    auto compute = [&](const Tile<U> &T, int it) {
+        const int row0 = it * ROWS_ITER + row_lane;
+        if (it < n_full) step<DT, D, GT, U, false>(T, q, st, c, row0, n);
+        else step<DT, D, GT, U, true>(T, q, st, c, row0, n);
+    };
+
+    // two register tiles, ping-pong: the loads of step it+1 are in flight
+    // while step it is computed
+    Tile<U> ta, tb;
+    issue(ta, 0);
+    for (int it = 0; it < n_iters; it += 2) {
+        if (it + 1 < n_iters) issue(tb, it + 1);
+        compute(ta, it);
+        if (it + 1 >= n_iters) break;
+        if (it + 2 < n_iters) issue(ta, it + 2);
+        compute(tb, it + 1);
+    }
+
+    // ---- merge the RPW row groups of this wave (lanes LPR apart)
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        const acc_t mw = across_groups_max<LPR>(st.m[h]);
+        const float f = (st.m[h] == mw) ? 1.0f : exp2_hw((float)(st.m[h] - mw));
+        st.m[h] = mw;
+        st.l[h] = across_groups_sum<LPR>(st.l[h] * f);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) st.o[h][e] = across_groups_sum<LPR>(st.o[h][e] * f);
+    }
+
+    // ---- merge the waves of the workgroup through LDS
+    __shared__ float lds_o[kWaves][GT][D];
+    __shared__ float lds_l[kWaves][GT];
+    __shared__ acc_t lds_m[kWaves][GT];
+    if (rg == 0) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) lds_o[w][h][sub * EPL + e] = st.o[h][e];
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int h = 0; h < GT; ++h) {
+            lds_m[w][h] = st.m[h];
+            lds_l[w][h] = st.l[h];
+        }
+    }
+    __syncthreads();
+
+    const int col = tid % D;
+    for (int h = tid / D; h < GT; h += kThreads / D) {
+        acc_t ms = lds_m[0][h];
+#pragma unroll
+        for (int ww = 1; ww < kWaves; ++ww) ms = fmax(ms, lds_m[ww][h]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) {
+            const acc_t mw = lds_m[ww][h];
+            const float f = (mw == ms) ? 1.0f : exp2_hw((float)(mw - ms));
+            lt = fmaf(f, lds_l[ww][h], lt);
+            ot = fmaf(f, lds_o[ww][h][col], ot);
+        }
+        // Natural-log units for the stored max.  The fp32 value written is not
+        // exactly ms*ln2, so l and o are rescaled by the (tiny) residual to stay
+        // consistent with the number a reader of part_m will see.
+        const float m_nat = (float)(ms * (acc_t)kLn2);
+        const acc_t resid = fma(-(acc_t)m_nat, (acc_t)kLog2e, ms);
+        const float fix = exp2_hw((float)resid);
+        const int64_t pidx = pidx0 + (int64_t)h * a.P;
+        a.part_o[pidx * D + col] = ot * fix;
+        if (col == 0) {
+            a.part_m[pidx] = m_nat;
+            a.part_l[pidx] = lt * fix;
+        }
+    }
+}
+
+template <int DT, int D, int GT>
+hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
+    constexpr int U = 4;
+    const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
+    hipLaunchKernelGGL((decode_partial_kernel<DT, D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int DT, int D>
+hipError_t launch_gt(const PartialArgs &a, int gt, hipStream_t s) {
+    switch (gt) {
+        case 8: return launch_one<DT, D, 8>(a, s);
+        case 4: return launch_one<DT, D, 4>(a, s);
+        case 2: return launch_one<DT, D, 2>(a, s);
+        default: return launch_one<DT, D, 1>(a, s);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s) {
+    const int gt = a.g / a.slices;
+    if (dtype == TA_BF16) return d == 128 ? launch_gt<TA_BF16, 128>(a, gt, s) : launch_gt<TA_BF16, 64>(a, gt, s);
+    return d == 128 ? launch_gt<TA_F32, 128>(a, gt, s) : launch_gt<TA_F32, 64>(a, gt, s);
+}
+
+}  // namespace ta

@@ -1,0 +1,76 @@
+// hbm_probe: stand-alone measurement aid, not part of the library.
+//   1. streaming-read ceiling of the box: a read-only kernel over a buffer far
+//      larger than the last-level cache (128-bit loads, several in flight);
+//   2. a plain copy kernel of known size, the reference against which the
+//      rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled.
+// usage: hbm_probe [MiB=2048] [iters=20]
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+
+#define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { \
+    fprintf(stderr, "%s:%d %s\n", __FILE__, __LINE__, hipGetErrorString(e_)); return 1; } } while (0)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// each workgroup reads a contiguous span; 4 independent 16-byte loads per lane per trip
+__global__ void __launch_bounds__(256) read_only(const v4i *__restrict__ src, size_t n_vec, int *sink) {
+    const size_t per_wg = n_vec / gridDim.x;            // host makes this a multiple of 1024
+    const v4i *p = src + per_wg * blockIdx.x + threadIdx.x;
+    v4i acc = {0, 0, 0, 0};
+    for (size_t i = 0; i < per_wg; i += 1024) {
+        v4i a = p[i], b = p[i + 256], c = p[i + 512], d = p[i + 768];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5eed1234) *sink = 1;   // keeps the loads alive
+}
+
+__global__ void __launch_bounds__(256) copy_plain(const v4i *__restrict__ src, v4i *__restrict__ dst, size_t n_vec) {
+    const size_t per_wg = n_vec / gridDim.x;
+    const size_t base = per_wg * blockIdx.x + threadIdx.x;
+    for (size_t i = 0; i < per_wg; i += 1024) {
+        v4i a = src[base + i], b = src[base + i + 256], c = src[base + i + 512], d = src[base + i + 768];
+        dst[base + i] = a; dst[base + i + 256] = b; dst[base + i + 512] = c; dst[base + i + 768] = d;
+    }
+}
+
+int main(int argc, char **argv) {
+    const size_t mib = argc > 1 ? strtoull(argv[1], nullptr, 10) : 2048;
+    const int iters = argc > 2 ? atoi(argv[2]) : 20;
+    const int grids[] = {2048, 4096, 8192};
+    size_t bytes = mib << 20;
+    bytes -= bytes % ((size_t)8192 * 1024 * 16);         // every grid gets whole 16 KiB trips
+    if (bytes == 0) { fprintf(stderr, "buffer too small\n"); return 1; }
+    const size_t n_vec = bytes / 16;
+    void *src, *dst; int *sink;
+    CHECK(hipMalloc(&src, bytes));
+    CHECK(hipMalloc(&dst, bytes));
+    CHECK(hipMalloc(&sink, 4));
+    CHECK(hipMemset(src, 1, bytes));
+    CHECK(hipMemset(dst, 0, bytes));
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+    printf("buffer %zu bytes, %d iterations\n", bytes, iters);
+    for (int g : grids) {
+        for (int i = 0; i < 3; ++i) read_only<<<g, 256>>>((const v4i *)src, n_vec, sink);
+        CHECK(hipEventRecord(e0));
+        for (int i = 0; i < iters; ++i) read_only<<<g, 256>>>((const v4i *)src, n_vec, sink);
+        CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
+        float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+        printf("read_only  grid %5d: %8.1f us  %8.1f GB/s read\n", g, ms * 1e3 / iters, bytes / (ms * 1e-3 / iters) / 1e9);
+    }
+    for (int g : grids) {
+        for (int i = 0; i < 3; ++i) copy_plain<<<g, 256>>>((const v4i *)src, (v4i *)dst, n_vec);
+        CHECK(hipEventRecord(e0));
+        for (int i = 0; i < iters; ++i) copy_plain<<<g, 256>>>((const v4i *)src, (v4i *)dst, n_vec);
+        CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
+        float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+        printf("copy_plain grid %5d: %8.1f us  %8.1f GB/s read+write (%zu B read, %zu B written per launch)\n",
+               g, ms * 1e3 / iters, 2.0 * bytes / (ms * 1e-3 / iters) / 1e9, bytes, bytes);
+    }
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipGetLastError());
+    hipFree(src); hipFree(dst); hipFree(sink);
+    return 0;
+}

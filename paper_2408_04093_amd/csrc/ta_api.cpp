@@ -1,0 +1,177 @@
+// C ABI of the decode-attention library: argument checks, chunk-count
+// heuristic and kernel launches.  All checks run on the host before any
+// launch; no pointer argument is dereferenced on the host except ta_problem.
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "ta_internal.hpp"
+
+namespace {
+
+using namespace ta;
+
+inline int elem_bytes(int dt) { return dt == TA_BF16 ? 2 : 4; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape / stride / dtype checks common to every entry point that takes a problem.
+ta_status check_problem(const ta_problem *p) {
+    if (!p) return TA_ERR_NULL;
+    if (p->qkv_dtype != TA_BF16 && p->qkv_dtype != TA_F32) return TA_ERR_DTYPE;
+    if (p->out_dtype != TA_BF16 && p->out_dtype != TA_F32) return TA_ERR_DTYPE;
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1) return TA_ERR_SHAPE;
+    if (p->Hq % p->Hkv != 0) return TA_ERR_SHAPE;
+    if (p->d != 64 && p->d != 128) return TA_ERR_UNSUPPORTED;
+    if (p->Hq / p->Hkv > 16) return TA_ERR_UNSUPPORTED;
+    if (!std::isfinite(p->scale)) return TA_ERR_SHAPE;
+    const int eb = elem_bytes(p->qkv_dtype);
+    const int64_t strides[6] = {p->k_stride_b, p->k_stride_h, p->k_stride_n,
+                                p->v_stride_b, p->v_stride_h, p->v_stride_n};
+    for (int64_t s : strides) {
+        if (s < 0) return TA_ERR_SHAPE;
+        if ((s * eb) % 16 != 0) return TA_ERR_ALIGN;
+    }
+    if (p->k_stride_n < p->d || p->v_stride_n < p->d) return TA_ERR_SHAPE;
+    // 32-bit byte offsets inside one [N, d] head slice
+    const int64_t lim = (int64_t)1 << 32;
+    if (p->N * p->k_stride_n * eb >= lim || p->N * p->v_stride_n * eb >= lim) return TA_ERR_UNSUPPORTED;
+    if ((int64_t)p->B * p->Hq >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    return TA_OK;
+}
+
+int device_compute_units() {
+    static std::once_flag once;
+    static int cus = 256;   // MI355X
+    std::call_once(once, [] {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+        (void)hipGetLastError();
+    });
+    return cus;
+}
+
+// Chunk count: aim at kWgPerCu workgroups per compute unit over the whole
+// launch, keep chunks between kMinChunk and kMaxChunk keys.
+int32_t suggest_chunks(const ta_problem *p, int cus) {
+    constexpr int64_t kWgPerCu = 8, kMinChunk = 256, kMaxChunk = 4096;
+    const int g = p->Hq / p->Hkv;
+    const int64_t groups = (int64_t)p->B * p->Hkv * (g / heads_per_workgroup(g));
+    int64_t P = (kWgPerCu * cus + groups - 1) / groups;
+    const int64_t p_hi = (p->N + kMinChunk - 1) / kMinChunk;   // no chunk shorter than kMinChunk
+    const int64_t p_lo = (p->N + kMaxChunk - 1) / kMaxChunk;   // none longer than kMaxChunk
+    if (P > p_hi) P = p_hi;
+    if (P < p_lo) P = p_lo;
+    if (P < 1) P = 1;
+    if (P > 65536) P = 65536;
+    return (int32_t)P;
+}
+
+size_t workspace_bytes(const ta_problem *p, int32_t P) {
+    const size_t floats = (size_t)p->B * p->Hq * (size_t)P * (size_t)(p->d + 2);
+    return (floats * sizeof(float) + 255) & ~(size_t)255;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ta_status_string(ta_status s) {
+    switch (s) {
+        case TA_OK: return "ok";
+        case TA_ERR_NULL: return "null pointer";
+        case TA_ERR_SHAPE: return "bad shape or stride";
+        case TA_ERR_DTYPE: return "bad dtype";
+        case TA_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+        case TA_ERR_WORKSPACE: return "workspace too small";
+        case TA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case TA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int32_t ta_suggest_chunks(const ta_problem *p) {
+    if (check_problem(p) != TA_OK) return 0;
+    return suggest_chunks(p, device_compute_units());
+}
+
+size_t ta_workspace_bytes(const ta_problem *p, int32_t P) {
+    if (check_problem(p) != TA_OK || P < 1) return 0;
+    return workspace_bytes(p, P);
+}
+
+ta_status ta_decode_partial(const ta_problem *p, const void *q, const void *K, const void *V,
+                            int32_t P, const int64_t *chunk_bounds,
+                            float *part_m, float *part_l, float *part_o, void *stream) {
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || !V || !part_m || !part_l || !part_o) return TA_ERR_NULL;
+    if (P < 1 || P > (1 << 20)) return TA_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(part_m) | reinterpret_cast<uintptr_t>(part_l) |
+         reinterpret_cast<uintptr_t>(part_o)) & 3u)
+        return TA_ERR_ALIGN;
+
+    const int eb = elem_bytes(p->qkv_dtype);
+    PartialArgs a{};
+    a.q = q; a.K = K; a.V = V;
+    a.valid_len = p->valid_len;
+    a.bounds = chunk_bounds;
+    a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
+    a.N = p->N;
+    a.t = (p->N + P - 1) / P;
+    a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
+    a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
+    a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
+    a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
+    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
+    a.g = p->Hq / p->Hkv;
+    a.slices = a.g / heads_per_workgroup(a.g);
+    a.c = (double)p->scale * kLog2e;
+    if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    return launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? TA_OK : TA_ERR_HIP;
+}
+
+ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
+                          const float *part_m, const float *part_l, const float *part_o,
+                          void *out, int32_t out_dtype, float *lse, void *stream) {
+    if (!part_m || !part_l || !part_o || !out || !lse) return TA_ERR_NULL;
+    if (out_dtype != TA_BF16 && out_dtype != TA_F32) return TA_ERR_DTYPE;
+    if (B < 1 || Hq < 1 || P < 1 || (int64_t)B * Hq >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    if (d != 64 && d != 128) return TA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(part_o) & 7u) || (reinterpret_cast<uintptr_t>(part_m) & 3u) ||
+        (reinterpret_cast<uintptr_t>(part_l) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
+        (reinterpret_cast<uintptr_t>(out) & (out_dtype == TA_BF16 ? 1u : 3u)))
+        return TA_ERR_ALIGN;
+    CombineArgs a{};
+    a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
+    a.out = out; a.lse = lse;
+    a.B = B; a.Hq = Hq; a.P = P;
+    a.out_dtype = out_dtype;
+    return launch_tree_combine(a, d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
+ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const void *V,
+                    void *workspace, size_t workspace_bytes_given,
+                    void *out, float *lse, void *stream) {
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || !V || !workspace || !out || !lse) return TA_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TA_ERR_ALIGN;
+    const int32_t P = suggest_chunks(p, device_compute_units());
+    if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
+
+    // workspace layout: part_o [B,Hq,P,d] | part_m [B,Hq,P] | part_l [B,Hq,P]
+    const size_t bhp = (size_t)p->B * p->Hq * (size_t)P;
+    float *part_o = static_cast<float *>(workspace);
+    float *part_m = part_o + bhp * p->d;
+    float *part_l = part_m + bhp;
+    ta_status s2 = ta_decode_partial(p, q, K, V, P, nullptr, part_m, part_l, part_o, stream);
+    if (s2 != TA_OK) return s2;
+    return ta_tree_combine(p->B, p->Hq, p->d, P, part_m, part_l, part_o, out, p->out_dtype, lse, stream);
+}
+
+}  // extern "C"

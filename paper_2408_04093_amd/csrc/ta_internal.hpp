@@ -1,0 +1,46 @@
+// Host-side launch descriptors shared by the API layer and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tree_attn.h"
+
+namespace ta {
+
+constexpr double kLog2e = 1.4426950408889634074;
+constexpr double kLn2 = 0.69314718055994530942;
+
+// Everything one decode_partial launch needs, passed by value.
+struct PartialArgs {
+    const void *q, *K, *V;
+    const int32_t *valid_len;   // device [B] or null
+    const int64_t *bounds;      // device [P+1] or null
+    float *part_m, *part_l, *part_o;
+    int64_t N;
+    int64_t t;                  // keys per chunk when bounds == null
+    int64_t k_sb, k_sh, v_sb, v_sh;   // elements
+    uint32_t k_row_bytes, v_row_bytes;
+    int32_t B, Hq, Hkv, P;
+    int32_t g;                  // Hq / Hkv
+    int32_t slices;             // g / heads-per-workgroup
+    double c;                   // scale * log2(e)
+};
+
+struct CombineArgs {
+    const float *part_m, *part_l, *part_o;
+    void *out;
+    float *lse;
+    int32_t B, Hq, P;
+    int32_t out_dtype;
+};
+
+// Heads of one GQA group handled by one workgroup for a given group size.
+inline int heads_per_workgroup(int g) {
+    for (int gt : {8, 4, 2}) if (g % gt == 0) return gt;
+    return 1;
+}
+
+hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
+hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
+
+}  // namespace ta

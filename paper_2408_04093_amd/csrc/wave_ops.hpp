@@ -1,0 +1,79 @@
+// Wavefront (64-lane) data-movement helpers for gfx950.  Device code only.
+//
+// A DPP "row" is 16 consecutive lanes.  Reductions inside a row use the DPP
+// modifier of the VALU add/max itself (no extra move, no LDS); anything that
+// crosses rows goes through ds_bpermute (__shfl_xor).
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace ta {
+
+constexpr int kWave = 64;
+
+// DPP controls (gfx9 encoding)
+constexpr int kDppXor1 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+    long long b = __double_as_longlong(x);
+    int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffLL), CTRL, 0xf, 0xf, true);
+    int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp(float x) { return dpp_f32<CTRL>(x); }
+template <int CTRL> __device__ __forceinline__ double dpp(double x) { return dpp_f64<CTRL>(x); }
+
+// Sum over groups of LANES consecutive lanes (LANES in {8,16,32}); every lane
+// of the group ends with the total.  After the two quad steps all four lanes
+// of a quad agree, so the mirror steps pair up whole quads.
+template <int LANES, typename F>
+__device__ __forceinline__ F group_sum(F x) {
+    x += dpp<kDppXor1>(x);
+    x += dpp<kDppXor2>(x);
+    x += dpp<kDppHalfMirror>(x);
+    if constexpr (LANES >= 16) x += dpp<kDppMirror>(x);
+    if constexpr (LANES >= 32) x += __shfl_xor(x, 16);
+    return x;
+}
+
+// Reductions across the groups of a wave (lane distance >= LANES).
+template <int LANES, typename F>
+__device__ __forceinline__ F across_groups_max(F x) {
+#pragma unroll
+    for (int off = LANES; off < kWave; off <<= 1) x = fmax(x, __shfl_xor(x, off));
+    return x;
+}
+template <int LANES, typename F>
+__device__ __forceinline__ F across_groups_sum(F x) {
+#pragma unroll
+    for (int off = LANES; off < kWave; off <<= 1) x += __shfl_xor(x, off);
+    return x;
+}
+
+// Whole-wave reductions (used by the combine kernel).
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    return x;
+}
+
+// 2^x on the hardware transcendental unit (v_exp_f32, about 1 ulp).
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// fp32 -> bf16 bits, round to nearest even.  Input must be finite or +-inf.
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float x) {
+    unsigned int u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+}  // namespace ta

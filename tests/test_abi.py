@@ -1,0 +1,118 @@
+"""The C-ABI library: exported symbols and host-side argument checks (no GPU work).
+
+Every check in the library runs before anything is launched, so the error
+paths can be driven from a machine without a GPU using fake, never-dereferenced
+device addresses.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2408_04093_amd as ta
+from paper_2408_04093_amd import build as ta_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tree_attn.h")
+FAKE = 0x1000  # 16-byte (and 256-byte) aligned, never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ta.lib_path()):
+        ta_build.build()
+    return ta.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ta_[a-z_]+)\s*\(", text)))
+
+
+def llama_problem():
+    p = ta.Problem()
+    p.B, p.Hq, p.Hkv, p.d, p.N = 1, 32, 8, 128, 131072
+    p.k_stride_n = p.v_stride_n = 128
+    p.k_stride_h = p.v_stride_h = 131072 * 128
+    p.k_stride_b = p.v_stride_b = 8 * 131072 * 128
+    p.qkv_dtype, p.out_dtype, p.scale = ta.TA_BF16, ta.TA_BF16, 128 ** -0.5
+    return p
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_functions() == sorted([
+        "ta_status_string", "ta_suggest_chunks", "ta_workspace_bytes",
+        "ta_decode_partial", "ta_tree_combine", "ta_decode"])
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    # 4 int32, 7 int64, 2 int32, float (+pad), pointer
+    assert ctypes.sizeof(ta.Problem) == 16 + 56 + 8 + 8 + 8
+    assert ta.Problem.valid_len.offset == 88 and ta.Problem.scale.offset == 80
+
+
+def test_status_strings(lib):
+    names = [ta.ta_status_string(c) for c in range(8)]
+    assert len(set(names)) == 8 and names[0] == "ok"
+    assert ta.ta_status_string(99) == "unknown status"
+
+
+def test_workspace_and_chunk_heuristic(lib):
+    p = llama_problem()
+    P = ta.ta_suggest_chunks(p)
+    assert 32 <= P <= 512
+    assert ta.ta_workspace_bytes(p, P) >= 32 * P * 130 * 4
+    assert ta.ta_workspace_bytes(p, P) % 256 == 0
+    assert ta.ta_workspace_bytes(p, 0) == 0
+    p.N = 64               # tiny: never more chunks than keys / 256, at least one
+    assert ta.ta_suggest_chunks(p) == 1
+    p.d = 96
+    assert ta.ta_suggest_chunks(p) == 0 and ta.ta_workspace_bytes(p, 4) == 0
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "d", 96), 6),
+    (lambda p: setattr(p, "Hq", 30), 2),
+    (lambda p: setattr(p, "Hkv", 1), 6),             # group of 32 heads
+    (lambda p: setattr(p, "N", 0), 2),
+    (lambda p: setattr(p, "qkv_dtype", 7), 3),
+    (lambda p: setattr(p, "k_stride_n", 132), 4),    # rows no longer 16-byte aligned
+    (lambda p: setattr(p, "v_stride_n", 64), 2),     # rows overlap
+    (lambda p: setattr(p, "scale", float("nan")), 2),
+    (lambda p: setattr(p, "N", 1 << 25), 6),         # head slice >= 4 GiB
+])
+def test_bad_problems_are_refused_before_launch(lib, mutate, code):
+    p = llama_problem()
+    mutate(p)
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == code
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 4, None, FAKE, FAKE, FAKE, None) == code
+
+
+def test_null_alignment_and_workspace_errors(lib):
+    p = llama_problem()
+    need = ta.ta_workspace_bytes(p, ta.ta_suggest_chunks(p))
+    assert ta.ta_decode(p, None, FAKE, FAKE, FAKE, need, FAKE, FAKE, None) == 1
+    assert ta.ta_decode(p, FAKE, FAKE + 8, FAKE, FAKE, need, FAKE, FAKE, None) in (4,)
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE + 16, need, FAKE, FAKE, None) == 4
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, need - 1, FAKE, FAKE, None) == 5
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 0, None, FAKE, FAKE, FAKE, None) == 2
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 4, None, None, FAKE, FAKE, None) == 1
+    assert ta.ta_tree_combine(1, 32, 128, 4, FAKE, FAKE, None, FAKE, 0, FAKE, None) == 1
+    assert ta.ta_tree_combine(1, 32, 96, 4, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == 6
+    assert ta.ta_tree_combine(1, 32, 128, 0, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == 2
+    assert ta.ta_tree_combine(1, 32, 128, 4, FAKE, FAKE, FAKE, FAKE, 5, FAKE, None) == 3
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2408_04093_amd import _ffi
+    monkeypatch.setattr(_ffi, "_lib", None)
+    monkeypatch.setattr(_ffi, "_LIB_PATH", "/nonexistent/libtree_attn.so")
+    with pytest.raises(ImportError, match="no CPU fallback"):
+        _ffi.load()
