@@ -53,13 +53,21 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
+// Reinterpret one 32-bit register as two bf16.  Takes the value, not a vector
+// subscript: bit-casting `vec[i]` directly loses the index in this compiler.
+__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t x) {
+    bf16x2 r;
+    __builtin_memcpy(&r, &x, sizeof r);
+    return r;
+}
+
 // partial dot product of this lane's 16 bytes of a key row with q
 __device__ __forceinline__ float lane_dot(const v4i &k, const uint32_t (&q)[4]) {
-    float acc = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, k[r]),
-                                              __builtin_bit_cast(bf16x2, q[r]), acc, false);
+    const uint32_t k0 = (uint32_t)k.x, k1 = (uint32_t)k.y, k2 = (uint32_t)k.z, k3 = (uint32_t)k.w;
+    float acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k0), as_bf16x2(q[0]), 0.f, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k1), as_bf16x2(q[1]), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k2), as_bf16x2(q[2]), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k3), as_bf16x2(q[3]), acc, false);
     return acc;
 }
 __device__ __forceinline__ double lane_dot(const v4i &k, const double (&q)[4]) {
