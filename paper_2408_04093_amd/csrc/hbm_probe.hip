@@ -26,6 +26,19 @@ __global__ void __launch_bounds__(256) read_only(const v4i *__restrict__ src, si
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5eed1234) *sink = 1;   // keeps the loads alive
 }
 
+// the same read-only stream with non-temporal 128-bit loads
+__global__ void __launch_bounds__(256) read_only_nt(const v4i *__restrict__ src, size_t n_vec, int *sink) {
+    const size_t per_wg = n_vec / gridDim.x;
+    const v4i *p = src + per_wg * blockIdx.x + threadIdx.x;
+    v4i acc = {0, 0, 0, 0};
+    for (size_t i = 0; i < per_wg; i += 1024) {
+        v4i a = __builtin_nontemporal_load(p + i), b = __builtin_nontemporal_load(p + i + 256);
+        v4i c = __builtin_nontemporal_load(p + i + 512), d = __builtin_nontemporal_load(p + i + 768);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x5eed1234) *sink = 1;
+}
+
 __global__ void __launch_bounds__(256) copy_plain(const v4i *__restrict__ src, v4i *__restrict__ dst, size_t n_vec) {
     const size_t per_wg = n_vec / gridDim.x;
     const size_t base = per_wg * blockIdx.x + threadIdx.x;
@@ -38,7 +51,7 @@ __global__ void __launch_bounds__(256) copy_plain(const v4i *__restrict__ src, v
 int main(int argc, char **argv) {
     const size_t mib = argc > 1 ? strtoull(argv[1], nullptr, 10) : 2048;
     const int iters = argc > 2 ? atoi(argv[2]) : 20;
-    const int grids[] = {2048, 4096, 8192};
+    const int grids[] = {512, 1024, 2048, 4096, 8192};
     size_t bytes = mib << 20;
     bytes -= bytes % ((size_t)8192 * 1024 * 16);         // every grid gets whole 16 KiB trips
     if (bytes == 0) { fprintf(stderr, "buffer too small\n"); return 1; }
@@ -59,6 +72,14 @@ int main(int argc, char **argv) {
         CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
         float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
         printf("read_only  grid %5d: %8.1f us  %8.1f GB/s read\n", g, ms * 1e3 / iters, bytes / (ms * 1e-3 / iters) / 1e9);
+    }
+    for (int g : grids) {
+        for (int i = 0; i < 3; ++i) read_only_nt<<<g, 256>>>((const v4i *)src, n_vec, sink);
+        CHECK(hipEventRecord(e0));
+        for (int i = 0; i < iters; ++i) read_only_nt<<<g, 256>>>((const v4i *)src, n_vec, sink);
+        CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
+        float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+        printf("read_only_nt grid %5d: %8.1f us  %8.1f GB/s read (non-temporal loads)\n", g, ms * 1e3 / iters, bytes / (ms * 1e-3 / iters) / 1e9);
     }
     for (int g : grids) {
         for (int i = 0; i < 3; ++i) copy_plain<<<g, 256>>>((const v4i *)src, (v4i *)dst, n_vec);

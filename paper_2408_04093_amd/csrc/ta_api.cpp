@@ -35,7 +35,7 @@ ta_status check_problem(const ta_problem *p) {
     // 32-bit byte offsets inside one [N, d] head slice
     const int64_t lim = (int64_t)1 << 32;
     if (p->N * p->k_stride_n * eb >= lim || p->N * p->v_stride_n * eb >= lim) return TA_ERR_UNSUPPORTED;
-    if ((int64_t)p->B * p->Hq >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    if ((int64_t)p->B * p->Hq >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
     return TA_OK;
 }
 
@@ -53,17 +53,29 @@ int device_compute_units() {
     return cus;
 }
 
-// Chunk count: aim at kWgPerCu workgroups per compute unit over the whole
-// launch, keep chunks between kMinChunk and kMaxChunk keys.
+// Chunk count.  A launch runs in "rounds" of slots = CUs x resident workgroups
+// per CU.  Measured on MI355X: a partial last round costs a full one, chunks of
+// about 4096 keys amortise a workgroup's start-up, and beyond one round more
+// rounds even out the finishing times.  So: a whole number of rounds when the
+// (batch, kv head) count divides the slots, chunks near kTargetChunk keys, and
+// never shorter than kMinChunk.
 int32_t suggest_chunks(const ta_problem *p, int cus) {
-    constexpr int64_t kWgPerCu = 8, kMinChunk = 256, kMaxChunk = 4096;
+    constexpr int64_t kTargetChunk = 4096, kMinChunk = 256;
     const int g = p->Hq / p->Hkv;
-    const int64_t groups = (int64_t)p->B * p->Hkv * (g / heads_per_workgroup(g));
-    int64_t P = (kWgPerCu * cus + groups - 1) / groups;
-    const int64_t p_hi = (p->N + kMinChunk - 1) / kMinChunk;   // no chunk shorter than kMinChunk
-    const int64_t p_lo = (p->N + kMaxChunk - 1) / kMaxChunk;   // none longer than kMaxChunk
+    const int gt = heads_per_workgroup(g);
+    const int64_t groups = (int64_t)p->B * p->Hkv * (g / gt);
+    const int64_t slots = (int64_t)cus * decode_partial_occupancy(p->qkv_dtype, p->d, gt);
+    const int64_t per_round = slots / groups;              // chunks per group in one round
+    int64_t P;
+    if (per_round >= 1) {
+        int64_t rounds = (p->N + per_round * kTargetChunk / 2) / (per_round * kTargetChunk);
+        if (rounds < 1) rounds = 1;
+        P = per_round * rounds;
+    } else {
+        P = (p->N + kTargetChunk - 1) / kTargetChunk;
+    }
+    const int64_t p_hi = (p->N + kMinChunk - 1) / kMinChunk;
     if (P > p_hi) P = p_hi;
-    if (P < p_lo) P = p_lo;
     if (P < 1) P = 1;
     if (P > 65536) P = 65536;
     return (int32_t)P;
@@ -140,9 +152,9 @@ ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
                           void *out, int32_t out_dtype, float *lse, void *stream) {
     if (!part_m || !part_l || !part_o || !out || !lse) return TA_ERR_NULL;
     if (out_dtype != TA_BF16 && out_dtype != TA_F32) return TA_ERR_DTYPE;
-    if (B < 1 || Hq < 1 || P < 1 || (int64_t)B * Hq >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    if (B < 1 || Hq < 1 || P < 1 || (int64_t)B * Hq >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
     if (d != 64 && d != 128) return TA_ERR_UNSUPPORTED;
-    if ((reinterpret_cast<uintptr_t>(part_o) & 7u) || (reinterpret_cast<uintptr_t>(part_m) & 3u) ||
+    if ((reinterpret_cast<uintptr_t>(part_o) & 3u) || (reinterpret_cast<uintptr_t>(part_m) & 3u) ||
         (reinterpret_cast<uintptr_t>(part_l) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
         (reinterpret_cast<uintptr_t>(out) & (out_dtype == TA_BF16 ? 1u : 3u)))
         return TA_ERR_ALIGN;

@@ -41,6 +41,8 @@ inline int heads_per_workgroup(int g) {
 }
 
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
+// resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
+int decode_partial_occupancy(int dtype, int d, int gt);
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 
 }  // namespace ta

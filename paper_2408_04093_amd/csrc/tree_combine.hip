@@ -6,11 +6,13 @@
 //     m* = max_j m_j;  w_j = exp(m_j - m*);  l* = sum w_j l_j;  o* = sum w_j o_j
 //     out = o* / l*;   lse = m* + log l*
 //
-// One workgroup of 4 waves per (b, h).  The max over j is a log-depth
-// wavefront reduction; the weighted sums stream the P x d partial tile with
-// coalesced row reads, each wave taking every 4th partial, several rows in
-// flight; the 4 wave results meet in LDS.  The work is KB-to-MB sized and
-// latency-bound.
+// The work is KB-to-MB sized and latency-bound, so the kernel is laid out for
+// few dependent memory round trips and many workgroups: one workgroup per
+// (b, h, 32-column slice); its 256 threads are 8 groups of 32 lanes, group r
+// taking partials j = r, r+8, ... with up to 8 rows in flight per thread, the
+// first batch fetched before anything else.  max and the sum of l are
+// log-depth wavefront reductions finished in LDS; the weights w_j are staged
+// in LDS once per 1024 partials.
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
@@ -19,102 +21,118 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
+constexpr int kSlice = 32;                   // columns per workgroup (one 128-byte line per row)
+constexpr int kGroups = kThreads / kSlice;   // partial groups per workgroup
+constexpr int kBatch = 8;                    // rows in flight per thread
+constexpr int kTile = 1024;                  // weights staged in LDS at a time
+
+__device__ __forceinline__ float block_reduce(float x, float *sh, bool is_max) {
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float y = __shfl_xor(x, off);
+        x = is_max ? fmaxf(x, y) : x + y;
+    }
+    __syncthreads();            // sh may still be read from a previous call
+    if (lane == 0) sh[w] = x;
+    __syncthreads();
+    float r = sh[0];
+#pragma unroll
+    for (int ww = 1; ww < kWaves; ++ww) r = is_max ? fmaxf(r, sh[ww]) : r + sh[ww];
+    return r;
+}
 
 template <int D>
 __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArgs a) {
-    constexpr int CPL = D / kWave;   // columns per lane: 2 (d=128) or 1 (d=64)
     constexpr float kLog2eF = 1.4426950408889634074f;
+    constexpr int kSlices = D / kSlice;
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t bh = blockIdx.x;
+    const int c = tid & (kSlice - 1);
+    const int r = tid / kSlice;
+    const int64_t bh = blockIdx.x / kSlices;
+    const int col = (blockIdx.x % kSlices) * kSlice + c;
     const int P = a.P;
     const float *pm = a.part_m + bh * P;
     const float *pl = a.part_l + bh * P;
-    const float *po = a.part_o + bh * P * D;
+    const float *po = a.part_o + bh * P * D + col;
 
-    __shared__ float red_m[kWaves];
-    __shared__ float red_l[kWaves];
-    __shared__ float red_o[kWaves][D];
+    __shared__ float sh_red[kWaves];
+    __shared__ float sh_w[kTile];
+    __shared__ float sh_o[kGroups][kSlice];
+
+    // first batch of numerator rows: in flight while the max is being found
+    float x0[kBatch];
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+        const int j = r + i * kGroups;
+        x0[i] = j < P ? po[(int64_t)j * D] : 0.f;
+    }
 
     // m* = max over partials that hold keys (l_j > 0)
     float mx = -__builtin_huge_valf();
-    for (int j = tid; j < P; j += kThreads) {
-        const float mj = pm[j];
-        if (pl[j] > 0.f) mx = fmaxf(mx, mj);
-    }
-    mx = wave_max(mx);
-    if (lane == 0) red_m[w] = mx;
-    __syncthreads();
-    float mstar = red_m[0];
-#pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) mstar = fmaxf(mstar, red_m[ww]);
+    for (int j = tid; j < P; j += kThreads)
+        if (pl[j] > 0.f) mx = fmaxf(mx, pm[j]);
+    const float mstar = block_reduce(mx, sh_red, true);
 
-    if (mstar == -__builtin_huge_valf()) {   // no key anywhere: defined as out = 0, lse = -inf
-        if (tid < D) {
-            if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[bh * D + tid] = 0;
-            else reinterpret_cast<float *>(a.out)[bh * D + tid] = 0.f;
+    if (mstar == -__builtin_huge_valf()) {   // no key anywhere: out = 0, lse = -inf by definition
+        if (tid < kSlice) {
+            if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[bh * D + col] = 0;
+            else reinterpret_cast<float *>(a.out)[bh * D + col] = 0.f;
         }
-        if (tid == 0) a.lse[bh] = -__builtin_huge_valf();
+        if (tid == 0 && blockIdx.x % kSlices == 0) a.lse[bh] = -__builtin_huge_valf();
         return;
     }
 
-    // weighted sums; wave w takes partials j = w, w+4, ...; UN rows are
-    // fetched before any is consumed so their latencies overlap
-    constexpr int UN = 8;
-    float acc[CPL] = {};
-    float lsum = 0.f;
-    for (int j0 = w; j0 < P; j0 += kWaves * UN) {
-        float x[UN][CPL];
-        float wj[UN], lj[UN];
+    float acc = 0.f, lsum = 0.f;
+    for (int t0 = 0; t0 < P; t0 += kTile) {
+        const int tn = P - t0 < kTile ? P - t0 : kTile;
+        if (t0) __syncthreads();
+        for (int j = tid; j < tn; j += kThreads) {
+            const float lj = pl[t0 + j];
+            const float wj = lj > 0.f ? exp2_hw((pm[t0 + j] - mstar) * kLog2eF) : 0.f;
+            sh_w[j] = wj;
+            lsum = fmaf(wj, lj, lsum);
+        }
+        __syncthreads();
+        for (int j0 = r; j0 < tn; j0 += kGroups * kBatch) {
+            float x[kBatch];
+            if (t0 == 0 && j0 == r) {
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int j = j0 + i * kWaves;
-            const bool ok = j < P;
-            const int jj = ok ? j : w;          // any valid row; its weight is 0
-            lj[i] = pl[jj];                     // wave-uniform scalar loads
-            const float mj = pm[jj];
-            wj[i] = (ok && lj[i] > 0.f) ? exp2_hw((mj - mstar) * kLog2eF) : 0.f;
-            const float *row = po + (int64_t)jj * D + lane * CPL;
-            if constexpr (CPL == 2) {
-                const float2 v = *reinterpret_cast<const float2 *>(row);
-                x[i][0] = v.x;
-                x[i][1] = v.y;
+                for (int i = 0; i < kBatch; ++i) x[i] = x0[i];
             } else {
-                x[i][0] = row[0];
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i) {
+                    const int j = j0 + i * kGroups;
+                    x[i] = j < tn ? po[(int64_t)(t0 + j) * D] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int j = j0 + i * kGroups;
+                if (j < tn) acc = fmaf(sh_w[j], x[i], acc);
             }
         }
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            lsum = fmaf(wj[i], lj[i], lsum);
-#pragma unroll
-            for (int e = 0; e < CPL; ++e) acc[e] = fmaf(wj[i], x[i][e], acc[e]);
-        }
     }
-#pragma unroll
-    for (int e = 0; e < CPL; ++e) red_o[w][lane * CPL + e] = acc[e];
-    if (lane == 0) red_l[w] = lsum;
-    __syncthreads();
+    const float lstar = block_reduce(lsum, sh_red, false);
 
-    float lstar = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) lstar += red_l[ww];
-    if (tid < D) {
+    sh_o[r][c] = acc;
+    __syncthreads();
+    if (tid < kSlice) {
         float o = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) o += red_o[ww][tid];
+        for (int rr = 0; rr < kGroups; ++rr) o += sh_o[rr][tid];
         const float z = o / lstar;
-        if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[bh * D + tid] = f32_to_bf16_rne(z);
-        else reinterpret_cast<float *>(a.out)[bh * D + tid] = z;
+        if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[bh * D + col] = f32_to_bf16_rne(z);
+        else reinterpret_cast<float *>(a.out)[bh * D + col] = z;
     }
-    if (tid == 0) a.lse[bh] = mstar + logf(lstar);
+    if (tid == 0 && blockIdx.x % kSlices == 0) a.lse[bh] = mstar + logf(lstar);
 }
 
 }  // namespace
 
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
-    const dim3 grid((uint32_t)((int64_t)a.B * a.Hq));
+    const dim3 grid((uint32_t)((int64_t)a.B * a.Hq * (d / kSlice)));
     if (d == 128) hipLaunchKernelGGL((tree_combine_kernel<128>), grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL((tree_combine_kernel<64>), grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();

@@ -11,8 +11,9 @@ bits already costs 1.5e-3..2e-3 rel-L2 (more on an unlucky short row), so no
 implementation can promise 2e-3 per row.  Both sides therefore take the
 rounding decision in the same way: the GPU's bf16 output must equal
 round-to-nearest-even of its own fp32 output bit for bit, must be within one
-bf16 ulp of round-to-nearest-even of the oracle everywhere (differing on at
-most 0.5% of elements, where the fp32 value sits on a rounding boundary), and
+bf16 ulp of round-to-nearest-even of the oracle everywhere (or within 1e-4 of
+the row's rms for elements far below the row's scale), differing on at most
+0.5% of elements (where the fp32 value sits on a rounding boundary), and
 its rel-L2 over the whole tensor must be <= 2e-3 once the tensor is large
 enough (>= 2048 elements) for that statistic to be stable.
 """
@@ -50,7 +51,8 @@ def row_rel_l2(x, ref):
 def lse_err(lse, ref):
     lse = np.asarray(lse, np.float64)
     both_inf = np.isneginf(lse) & np.isneginf(ref)
-    d = np.where(both_inf, 0.0, np.abs(lse - ref))
+    with np.errstate(invalid="ignore"):
+        d = np.where(both_inf, 0.0, np.abs(lse - ref))
     return float(np.nan_to_num(d, nan=np.inf).max()) if d.size else 0.0
 
 
@@ -76,7 +78,10 @@ def check_bf16_output(out_b, out_f32, ref_out):
     np.testing.assert_array_equal(out_b, rne)
     ref_b = torch.from_numpy(np.ascontiguousarray(ref_out)).to(torch.bfloat16).float().numpy()
     ulp = np.abs(bf16_ordinal(out_b) - bf16_ordinal(ref_b))
-    assert ulp.max() <= 1
+    # elements far below the row's scale carry the row's absolute fp32 error, which is many of THEIR ulps
+    rms = np.sqrt((ref_out ** 2).mean(axis=-1, keepdims=True))
+    small = np.abs(out_b - ref_b) <= 1e-4 * rms
+    assert ((ulp <= 1) | small).all()
     assert (ulp != 0).sum() <= 1 + 0.005 * ulp.size
     if ref_out.size >= 2048:
         assert np.linalg.norm(out_b - ref_out) / np.linalg.norm(ref_out) <= TOL_BF16
@@ -157,7 +162,7 @@ def test_shapes_and_ragged_tails(dt, B, Hq, Hkv, d, N):
         assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
 
 
-def test_valid_len_zero_full_and_ragged():
+def test_valid_len_zero_whole_and_ragged():
     w = W.make_qkv(5, 8, 2, 128, 700, torch.bfloat16, seed=99, device="cuda")
     w.valid_len = torch.tensor([0, 700, 1, 333, 64], dtype=torch.int32, device="cuda")
     # poison the padding: it must never be read
