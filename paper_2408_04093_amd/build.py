@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtree_attn.so")
-SOURCES = ["ta_api.cpp", "decode_partial.hip", "tree_combine.hip"]
+SOURCES = ["ta_api.cpp", "decode_partial.hip", "decode_partial_mfma.hip", "tree_combine.hip"]
 HEADERS = ["ta_internal.hpp", "wave_ops.hpp"]
 
 FLAGS = [

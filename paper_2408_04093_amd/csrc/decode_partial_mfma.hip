@@ -1,0 +1,337 @@
+// decode_partial on the matrix cores: bf16 K/V, d = 128, up to 16 query heads
+// per KV head in one pass.  Same contract as the VALU kernel in
+// decode_partial.hip (Tree Attention, arXiv 2408.04093, Algorithm 3 steps 1-2:
+// per-chunk partial (m, l, o); Section 3 recurrence with the Appendix F max
+// shift), different arithmetic engine.
+//
+// Why MFMA here although the kernel is HBM-bound: with all heads of a GQA
+// group sharing one K/V stream, the VALU form needs ~74 vector instructions
+// per KB streamed at g = 4 (dot2 + cross-lane reductions + per-head exp/FMA)
+// and twice that at g = 8 -- it measured ~80 % VALU-busy at g = 4 and
+// VALU-bound (3.9 TB/s) at g = 8.  QK^T and PV as 16x16x32 bf16 MFMAs with
+// the head dimension padded to the 16-row tile cost the same for any g <= 16
+// and leave ~10 vector instructions per KB.
+//
+// Per wave and step: a tile of 32 keys (8 KB of K, 8 KB of V).
+//   K   global --(8 coalesced 128-bit nt loads: 16 lanes x 16 B = one row)-->
+//       VGPR --> LDS, row pitch 272 B --> VGPR in MFMA A layout
+//       (lane (kb = l/16, m = l%16) reads key m, bytes 16*(4t+kb) of step t;
+//       the 16-byte pad makes these reads bank-conflict-free).
+//       S[key][head] = sum_t A_t(K) x B_t(Q^T): 2 key groups x 4 k-steps.
+//   D layout of S: lane (r = l/16, h = l%16) holds keys 16G + 4r + i of head h,
+//       i.e. each lane owns 8 keys of ONE head: exactly the A layout needed
+//       for P in  O[head][col] += P[head][key] x V[key][col].
+//   V   stays in the registers it was loaded into.  Lane (r, c = l%16) loaded
+//       columns 8c..8c+7 of the 8 keys that lanes of row r own, so for each of
+//       its 8 columns j the lane already holds the 8 keys of B_j[k][n = c];
+//       a 16-bit interleave of register pairs puts them in B layout.  8 MFMAs
+//       (one per j) cover all 128 columns: acc_j[i] = O[head 4r+i][col 8c+j].
+//   P is split into bf16 hi + bf16 lo (two MFMAs per j) so that the
+//       probabilities keep 16 significant bits; rounding P to one bf16 would
+//       cost ~1e-3 relative error in the output.
+// The contraction order of keys inside a tile is a fixed permutation
+// (kappa below) applied to P and V alike.
+#include "ta_internal.hpp"
+#include "wave_ops.hpp"
+
+namespace ta {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#ifndef TA_AUX
+#define TA_AUX 2   // non-temporal K/V loads
+#endif
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int D = 128;
+constexpr int kTile = 32;                       // keys per wave step
+constexpr int kPitch = 272;                     // LDS bytes per staged K row
+constexpr int kStage = kTile * kPitch;          // per wave
+constexpr int kMaxHeads = 16;
+
+// tile row owned by (row group r, slot e): e = 4G + i  ->  16G + 4r + i
+__device__ __forceinline__ int kappa(int r, int e) { return 16 * (e >> 2) + 4 * r + (e & 3); }
+
+__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
+    bf16x2 p = {(__bf16)a, (__bf16)b};   // v_cvt_pk_bf16_f32, round to nearest even
+    uint32_t u;
+    __builtin_memcpy(&u, &p, 4);
+    return u;
+}
+
+__global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
+    __shared__ float lds_m[kWaves][kMaxHeads];
+    __shared__ float lds_l[kWaves][kMaxHeads];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane >> 4, c = lane & 15;     // row group / (column block or head)
+    const int gt = a.g;                         // heads of the group, all in this workgroup
+
+    uint32_t id = blockIdx.x;
+    const int chunk = id % (uint32_t)a.P;  id /= (uint32_t)a.P;
+    const int hk = id % (uint32_t)a.Hkv;
+    const int b = id / (uint32_t)a.Hkv;
+    const int hq0 = hk * gt;
+
+    int64_t L = a.N;
+    if (a.valid_len) {
+        L = a.valid_len[b];
+        L = L < 0 ? 0 : (L > a.N ? a.N : L);
+    }
+    int64_t lo, hi;
+    if (a.bounds) {
+        lo = a.bounds[chunk];
+        hi = a.bounds[chunk + 1];
+        lo = lo < 0 ? 0 : (lo > L ? L : lo);
+        hi = hi < lo ? lo : (hi > L ? L : hi);
+    } else {
+        lo = (int64_t)chunk * a.t;
+        lo = lo > L ? L : lo;
+        hi = lo + a.t;
+        hi = hi > L ? L : hi;
+    }
+    const int n = (int)(hi - lo);
+
+    const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
+    if (n <= 0) {   // empty chunk: the identity of the merge
+        for (int i = tid; i < gt * D; i += kThreads)
+            a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
+        if (tid < gt) {
+            a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
+            a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+        }
+        return;
+    }
+
+    // Q^T as MFMA B operand: lane (kb = r, head = c) holds q[head][32t + 8r .. +8], zero for padded heads
+    bf16x8 qb[4];
+    {
+        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + (c < gt ? c : 0)) * D + 8 * r) * 2;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
+            if (c >= gt) raw = v4i{0, 0, 0, 0};
+            qb[t] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * 2 + lo * (int64_t)a.k_row_bytes;
+    const char *vb = (const char *)a.V + ((int64_t)b * a.v_sb + (int64_t)hk * a.v_sh) * 2 + lo * (int64_t)a.v_row_bytes;
+    const __amdgpu_buffer_rsrc_t krs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(kb), 0, (int)((uint32_t)(n - 1) * a.k_row_bytes + D * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(vb), 0, (int)((uint32_t)(n - 1) * a.v_row_bytes + D * 2), 0x00020000);
+
+    constexpr int ROWS_ITER = kWaves * kTile;
+    const int n_iters = (n + ROWS_ITER - 1) / ROWS_ITER;
+    const int n_full = n / ROWS_ITER;
+
+    int trow[8];                // tile row of slot e for this lane
+    uint32_t koff[8], voff[8];  // byte offsets in iteration 0
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        trow[e] = kappa(r, e);
+        koff[e] = (uint32_t)(w * kTile + trow[e]) * a.k_row_bytes + c * 16;
+        voff[e] = (uint32_t)(w * kTile + trow[e]) * a.v_row_bytes + c * 16;
+    }
+    char *stage = smem + w * kStage;
+
+    auto issue_k = [&](v4i (&kr)[8], int it) {
+        if (it < n_full) {
+            const uint32_t inc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                kr[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[e] + inc), 0, TA_AUX);
+        } else {   // ragged last step: rows past the chunk are redirected to its last row
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int row = it * ROWS_ITER + w * kTile + trow[e];
+                row = row < n ? row : n - 1;
+                kr[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)((uint32_t)row * a.k_row_bytes + c * 16), 0, TA_AUX);
+            }
+        }
+    };
+    auto issue_v = [&](v4i (&vr)[8], int it) {
+        if (it < n_full) {
+            const uint32_t inc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                vr[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[e] + inc), 0, TA_AUX);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int row = it * ROWS_ITER + w * kTile + trow[e];
+                row = row < n ? row : n - 1;
+                vr[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)((uint32_t)row * a.v_row_bytes + c * 16), 0, TA_AUX);
+            }
+        }
+    };
+
+    const float cs = (float)a.c;            // scale * log2(e)
+    float m_run = -__builtin_huge_valf();   // running max of head c (log2 units), same in all 4 row groups
+    float l_run = 0.f;                      // this lane's share of the normaliser of head c
+    f32x4 acc[8];                           // acc[j][i] = O[head 4r+i][col 8c+j]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    v4i kr[8], vr[8];
+    issue_k(kr, 0);
+    issue_v(vr, 0);
+
+    for (int it = 0; it < n_iters; ++it) {
+        const bool masked = it >= n_full;
+        // ---- K tile: registers -> LDS (row-major, padded) -> A layout
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            *reinterpret_cast<v4i *>(stage + trow[e] * kPitch + c * 16) = kr[e];
+        if (it + 1 < n_iters) issue_k(kr, it + 1);    // next K tile in flight during this step
+
+        f32x4 s[2];
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+            v4i af[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                af[t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
+            s[G] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                s[G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), qb[t], s[G], 0, 0, 0);
+        }
+
+        // ---- online softmax for head c over this lane's 8 keys (slot e = 4G + i)
+        float sv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sv[e] = s[e >> 2][e & 3] * cs;
+            if (masked && it * ROWS_ITER + w * kTile + trow[e] >= n) sv[e] = -__builtin_huge_valf();
+        }
+        float mx = sv[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const bool up = mx > m_run;
+        if (__builtin_amdgcn_ballot_w64(up) != 0) {
+            // raise the running max: rare once the stream is warm
+            const float alpha = up ? exp2_hw(m_run - mx) : 1.0f;
+            m_run = up ? mx : m_run;
+            l_run *= alpha;
+            // acc[.][i] belongs to head 4r+i, whose alpha sits in lane (r, c' = 4r+i)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j][i] *= ai;
+            }
+        }
+        float p[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = exp2_hw(sv[e] - m_run);
+            if (masked && sv[e] == -__builtin_huge_valf()) p[e] = 0.f;
+            l_run += p[e];
+        }
+        // P = hi + lo, both bf16, as MFMA A operand: lane (r, head c), k = 8r + e
+        uint32_t ph[4], pl[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
+            const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
+            pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
+        }
+        const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
+        const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
+
+        // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t bj[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
+                bj[x] = (j & 1) ? ((v0 >> 16) | (v1 & 0xffff0000u)) : ((v0 & 0xffffu) | (v1 << 16));
+            }
+            const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbj, acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbj, acc[j], 0, 0, 0);
+        }
+        if (it + 1 < n_iters) issue_v(vr, it + 1);
+    }
+
+    // ---- per-wave totals: the normaliser of head c is spread over the 4 row groups
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+
+    // ---- merge the waves through LDS (the K staging area is free now)
+    __syncthreads();
+    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][gt][D]
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int h = 4 * r + i;
+        if (h < gt) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) lds_o[(w * gt + h) * D + 8 * c + j] = acc[j][i];
+        }
+    }
+    if (r == 0 && c < gt) {
+        lds_m[w][c] = m_run;
+        lds_l[w][c] = l_run;
+    }
+    __syncthreads();
+
+    const int col = tid % D;
+    for (int h = tid / D; h < gt; h += kThreads / D) {
+        float ms = lds_m[0][h];
+#pragma unroll
+        for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
+        float lt = 0.f, ot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) {
+            const float mw = lds_m[ww][h];
+            const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
+            lt = fmaf(f, lds_l[ww][h], lt);
+            ot = fmaf(f, lds_o[(ww * gt + h) * D + col], ot);
+        }
+        // natural-log units for the stored max; l and o follow the rounding of the stored value
+        const float m_nat = ms * (float)kLn2;
+        const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
+        const int64_t pidx = pidx0 + (int64_t)h * a.P;
+        a.part_o[pidx * D + col] = ot * fix;
+        if (col == 0) {
+            a.part_m[pidx] = m_nat;
+            a.part_l[pidx] = lt * fix;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, hipStream_t s) {
+    const int64_t blocks = (int64_t)a.B * a.Hkv * a.P;
+    hipLaunchKernelGGL(decode_partial_mfma_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+int decode_partial_mfma_occupancy() {
+    static const int cached = [] {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel, kThreads, 0) != hipSuccess ||
+            nb < 1) {
+            (void)hipGetLastError();
+            nb = 2;
+        }
+        return nb;
+    }();
+    return cached;
+}
+
+}  // namespace ta

@@ -62,9 +62,11 @@ int device_compute_units() {
 int32_t suggest_chunks(const ta_problem *p, int cus) {
     constexpr int64_t kTargetChunk = 4096, kMinChunk = 256;
     const int g = p->Hq / p->Hkv;
-    const int gt = heads_per_workgroup(g);
+    const int gt = heads_per_workgroup(p->qkv_dtype, p->d, g);
     const int64_t groups = (int64_t)p->B * p->Hkv * (g / gt);
-    const int64_t slots = (int64_t)cus * decode_partial_occupancy(p->qkv_dtype, p->d, gt);
+    const int occ = use_mfma_path(p->qkv_dtype, p->d) ? decode_partial_mfma_occupancy()
+                                                      : decode_partial_occupancy(p->qkv_dtype, p->d, gt);
+    const int64_t slots = (int64_t)cus * occ;
     const int64_t per_round = slots / groups;              // chunks per group in one round
     int64_t P;
     if (per_round >= 1) {
@@ -140,11 +142,13 @@ ta_status ta_decode_partial(const ta_problem *p, const void *q, const void *K, c
     a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
     a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
     a.g = p->Hq / p->Hkv;
-    a.slices = a.g / heads_per_workgroup(a.g);
+    a.slices = a.g / heads_per_workgroup(p->qkv_dtype, p->d, a.g);
     a.c = (double)p->scale * kLog2e;
     if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
-    return launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? TA_OK : TA_ERR_HIP;
+    const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
+                             ? launch_decode_partial_mfma(a, static_cast<hipStream_t>(stream))
+                             : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
 ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,

@@ -34,8 +34,13 @@ struct CombineArgs {
     int32_t out_dtype;
 };
 
+// bf16 with d = 128 runs on the matrix-core kernel (any group size up to 16 in
+// one pass); everything else on the VALU kernel.
+inline bool use_mfma_path(int dtype, int d) { return dtype == TA_BF16 && d == 128; }
+
 // Heads of one GQA group handled by one workgroup for a given group size.
-inline int heads_per_workgroup(int g) {
+inline int heads_per_workgroup(int dtype, int d, int g) {
+    if (use_mfma_path(dtype, d)) return g;
     for (int gt : {8, 4, 2}) if (g % gt == 0) return gt;
     return 1;
 }
@@ -43,6 +48,8 @@ inline int heads_per_workgroup(int g) {
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
 // resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
 int decode_partial_occupancy(int dtype, int d, int gt);
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, hipStream_t s);   // bf16, d = 128, slices = 1
+int decode_partial_mfma_occupancy();
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 
 }  // namespace ta
