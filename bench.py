@@ -90,14 +90,35 @@ def main():
     alg = algorithmic_bytes(w0)
 
     probs = [ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_BF16) for w in ws]
-    P = ta.ta_suggest_chunks(probs[0])
+    # the "combine" workload fixes its own P unequal chunks; the others use the library's choice
+    bounds = w0.chunk_bounds
+    P = bounds.numel() - 1 if bounds is not None else ta.ta_suggest_chunks(probs[0])
     wbytes = ta.ta_workspace_bytes(probs[0], P)
     workspace = torch.empty(wbytes, dtype=torch.uint8, device=dev)
     out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
+    bhp = B * Hq * P
+    part_o = workspace[:bhp * d * 4].view(torch.float32)
+    part_m = workspace[bhp * d * 4:bhp * (d + 1) * 4].view(torch.float32)
+    part_l = workspace[bhp * (d + 1) * 4:bhp * (d + 2) * 4].view(torch.float32)
+
+    def partial_only(i):
+        w, p = ws[i % n_copies], probs[i % n_copies]
+        rc = ta.ta_decode_partial(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), P,
+                                  bounds.data_ptr() if bounds is not None else None,
+                                  part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(), stream)
+        if rc:
+            raise ta.TAError(rc, "ta_decode_partial")
 
     def step(i):
+        if bounds is not None:
+            partial_only(i)
+            rc = ta.ta_tree_combine(B, Hq, d, P, part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(),
+                                    out.data_ptr(), ta.TA_BF16, lse.data_ptr(), stream)
+            if rc:
+                raise ta.TAError(rc, "ta_tree_combine")
+            return
         w, p = ws[i % n_copies], probs[i % n_copies]
         rc = ta.ta_decode(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), workspace.data_ptr(), wbytes,
                           out.data_ptr(), lse.data_ptr(), stream)
@@ -116,18 +137,6 @@ def main():
     gbps = alg / (ms_per_step * 1e-3) / 1e9
 
     # dominant kernel alone, same launch shape (same P), events on the launch stream
-    bhp = B * Hq * P
-    part_o = workspace[:bhp * d * 4].view(torch.float32)
-    part_m = workspace[bhp * d * 4:bhp * (d + 1) * 4].view(torch.float32)
-    part_l = workspace[bhp * (d + 1) * 4:bhp * (d + 2) * 4].view(torch.float32)
-
-    def partial_only(i):
-        w, p = ws[i % n_copies], probs[i % n_copies]
-        rc = ta.ta_decode_partial(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), P, None,
-                                  part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(), stream)
-        if rc:
-            raise ta.TAError(rc, "ta_decode_partial")
-
     for i in range(max(2, args.warmup // 4)):
         partial_only(i)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -149,7 +158,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w0.q.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
-                   "chunks_P": P, "kv_buffers_rotated": n_copies,
+                   "chunks_P": P, "chunking": "unequal table" if bounds is not None else "equal",
+                   "kv_buffers_rotated": n_copies,
                    "algorithmic_bytes_per_step": alg},
         "roofline": {"kernel": "decode_partial", "bound": "hbm", "achieved": round(ach, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),

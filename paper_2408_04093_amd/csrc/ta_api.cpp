@@ -53,28 +53,50 @@ int device_compute_units() {
     return cus;
 }
 
-// Chunk count.  A launch runs in "rounds" of slots = CUs x resident workgroups
-// per CU.  Measured on MI355X: a partial last round costs a full one, chunks of
-// about 4096 keys amortise a workgroup's start-up, and beyond one round more
-// rounds even out the finishing times.  So: a whole number of rounds when the
-// (batch, kv head) count divides the slots, chunks near kTargetChunk keys, and
-// never shorter than kMinChunk.
+// Chunk count (host-only heuristic, tuned on MI355X measurements).
+//
+// Matrix-core kernel (bf16, d = 128): with equal work per workgroup the best
+// launch is ONE workgroup per compute unit, each streaming one long contiguous
+// share (7.2 TB/s at 1M keys; two per CU or a ragged last round measured
+// 4-8 % slower).  So P = CUs / groups, times a whole number of rounds only
+// when a chunk would exceed kLongChunk keys.  If there are more (batch, kv
+// head) groups than CUs, or the batch is ragged (lengths live on the device
+// and are unknown here), the work is cut fine enough (>= 8 workgroups per CU,
+// chunks of kRaggedChunk keys) for the hardware dispatcher to balance it.
+//
+// VALU kernel (fp32 or d = 64): rounds of CUs x resident workgroups, chunks
+// near 4096 keys.
 int32_t suggest_chunks(const ta_problem *p, int cus) {
-    constexpr int64_t kTargetChunk = 4096, kMinChunk = 256;
+    constexpr int64_t kMinChunk = 256;
     const int g = p->Hq / p->Hkv;
     const int gt = heads_per_workgroup(p->qkv_dtype, p->d, g);
     const int64_t groups = (int64_t)p->B * p->Hkv * (g / gt);
-    const int occ = use_mfma_path(p->qkv_dtype, p->d) ? decode_partial_mfma_occupancy()
-                                                      : decode_partial_occupancy(p->qkv_dtype, p->d, gt);
-    const int64_t slots = (int64_t)cus * occ;
-    const int64_t per_round = slots / groups;              // chunks per group in one round
     int64_t P;
-    if (per_round >= 1) {
-        int64_t rounds = (p->N + per_round * kTargetChunk / 2) / (per_round * kTargetChunk);
-        if (rounds < 1) rounds = 1;
-        P = per_round * rounds;
+    if (use_mfma_path(p->qkv_dtype, p->d)) {
+        constexpr int64_t kLongChunk = 32768, kRaggedChunk = 1024, kBalancedChunk = 2048;
+        const int64_t per_round = cus / groups;
+        if (p->valid_len) {
+            P = (p->N + kRaggedChunk - 1) / kRaggedChunk;
+        } else if (per_round >= 1) {
+            int64_t rounds = (p->N + per_round * kLongChunk / 2) / (per_round * kLongChunk);
+            if (rounds < 1) rounds = 1;
+            P = per_round * rounds;
+        } else {
+            P = (8 * cus + groups - 1) / groups;
+            const int64_t p_bal = (p->N + kBalancedChunk - 1) / kBalancedChunk;
+            if (P > p_bal) P = p_bal;
+        }
     } else {
-        P = (p->N + kTargetChunk - 1) / kTargetChunk;
+        constexpr int64_t kTargetChunk = 4096;
+        const int64_t slots = (int64_t)cus * decode_partial_occupancy(p->qkv_dtype, p->d, gt);
+        const int64_t per_round = slots / groups;
+        if (per_round >= 1) {
+            int64_t rounds = (p->N + per_round * kTargetChunk / 2) / (per_round * kTargetChunk);
+            if (rounds < 1) rounds = 1;
+            P = per_round * rounds;
+        } else {
+            P = (p->N + kTargetChunk - 1) / kTargetChunk;
+        }
     }
     const int64_t p_hi = (p->N + kMinChunk - 1) / kMinChunk;
     if (P > p_hi) P = p_hi;
