@@ -1,0 +1,86 @@
+// Workgroup -> (batch, kv head, head slice, chunk) mapping and the key range of
+// the chunk.  Tree Attention (arXiv 2408.04093) Algorithm 3 step 1 with the
+// chunks handed to workgroups instead of devices.  Device code only.
+//
+// Launch order matters because the hardware dispatcher hands out workgroups
+// in index order: the index is chunk-major (all groups' chunk 0 first), so in
+// a ragged batch the empty chunks of short sequences sit at the end and leave
+// at once; with an explicit table of unequal chunks (P <= 256) the chunks are
+// visited largest first (longest-processing-time order), which keeps a big
+// chunk from starting late and running alone at the end.
+#pragma once
+#include "ta_internal.hpp"
+
+namespace ta {
+
+struct ChunkRange {
+    int b, hk, slice, chunk;
+    int64_t lo;   // first key of the chunk
+    int n;        // number of keys (0 = empty)
+};
+
+constexpr int kMaxRankedChunks = 256;
+
+__device__ __forceinline__ void clamp_bounds(const PartialArgs &a, int chunk, int64_t L, int64_t &lo, int64_t &hi) {
+    lo = a.bounds[chunk];
+    hi = a.bounds[chunk + 1];
+    lo = lo < 0 ? 0 : (lo > L ? L : lo);
+    hi = hi < lo ? lo : (hi > L ? L : hi);
+}
+
+// sh: at least kMaxRankedChunks + 1 ints of LDS.  Must be called by every
+// thread of the workgroup (it may synchronise).
+template <int THREADS>
+__device__ __forceinline__ ChunkRange select_chunk(const PartialArgs &a, int *sh) {
+    static_assert(THREADS >= kMaxRankedChunks, "one thread per ranked chunk");
+    ChunkRange c;
+    const uint32_t groups = (uint32_t)a.B * (uint32_t)a.Hkv * (uint32_t)a.slices;
+    uint32_t id = blockIdx.x;
+    const int rank = id / groups;
+    id %= groups;
+    c.slice = id % (uint32_t)a.slices;  id /= (uint32_t)a.slices;
+    c.hk = id % (uint32_t)a.Hkv;
+    c.b = id / (uint32_t)a.Hkv;
+
+    int64_t L = a.N;
+    if (a.valid_len) {
+        L = a.valid_len[c.b];
+        L = L < 0 ? 0 : (L > a.N ? a.N : L);
+    }
+    int64_t lo, hi;
+    c.chunk = rank;
+    if (a.bounds) {
+        if (a.P <= kMaxRankedChunks) {
+            // chunk with the rank-th largest size (ties by index): O(P) per thread, P threads
+            const int t = threadIdx.x;
+            int my = 0;
+            if (t < a.P) {
+                clamp_bounds(a, t, L, lo, hi);
+                my = (int)(hi - lo);
+                sh[t] = my;
+            }
+            __syncthreads();
+            if (t < a.P) {
+                int r = 0;
+                for (int j = 0; j < a.P; ++j) {
+                    const int sj = sh[j];
+                    r += (sj > my || (sj == my && j < t)) ? 1 : 0;
+                }
+                if (r == rank) sh[kMaxRankedChunks] = t;
+            }
+            __syncthreads();
+            c.chunk = sh[kMaxRankedChunks];
+        }
+        clamp_bounds(a, c.chunk, L, lo, hi);
+    } else {
+        lo = (int64_t)c.chunk * a.t;
+        lo = lo > L ? L : lo;
+        hi = lo + a.t;
+        hi = hi > L ? L : hi;
+    }
+    c.lo = lo;
+    c.n = (int)(hi - lo);
+    return c;
+}
+
+}  // namespace ta

@@ -24,6 +24,7 @@
 //         |score| does not cost precision; exponentials and sums in fp32.
 //   Scores are kept in log2 units (score * scale * log2 e) so the exponential
 //   is the bare v_exp_f32; the partial is converted to natural units on store.
+#include "chunking.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
@@ -195,32 +196,12 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int sub = lane % LPR, rg = lane / LPR;
 
-    // workgroup -> (batch, kv head, head slice, chunk); chunk varies fastest
-    uint32_t id = blockIdx.x;
-    const int chunk = id % (uint32_t)a.P;  id /= (uint32_t)a.P;
-    const int slice = id % (uint32_t)a.slices;  id /= (uint32_t)a.slices;
-    const int hk = id % (uint32_t)a.Hkv;
-    const int b = id / (uint32_t)a.Hkv;
-    const int hq0 = hk * a.g + slice * GT;
-
-    int64_t L = a.N;
-    if (a.valid_len) {
-        L = a.valid_len[b];
-        L = L < 0 ? 0 : (L > a.N ? a.N : L);
-    }
-    int64_t lo, hi;
-    if (a.bounds) {
-        lo = a.bounds[chunk];
-        hi = a.bounds[chunk + 1];
-        lo = lo < 0 ? 0 : (lo > L ? L : lo);
-        hi = hi < lo ? lo : (hi > L ? L : hi);
-    } else {
-        lo = (int64_t)chunk * a.t;
-        lo = lo > L ? L : lo;
-        hi = lo + a.t;
-        hi = hi > L ? L : hi;
-    }
-    const int n = (int)(hi - lo);
+    __shared__ int sh_rank[kMaxRankedChunks + 1];
+    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
+    const int hq0 = hk * a.g + cr.slice * GT;
+    const int64_t lo = cr.lo;
+    const int n = cr.n;
 
     const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
     if (n <= 0) {   // empty chunk: the identity of the merge

@@ -31,6 +31,7 @@
 //       cost ~1e-3 relative error in the output.
 // The contraction order of keys inside a tile is a fixed permutation
 // (kappa below) applied to P and V alike.
+#include "chunking.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
@@ -75,30 +76,12 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     const int r = lane >> 4, c = lane & 15;     // row group / (column block or head)
     const int gt = a.g;                         // heads of the group, all in this workgroup
 
-    uint32_t id = blockIdx.x;
-    const int chunk = id % (uint32_t)a.P;  id /= (uint32_t)a.P;
-    const int hk = id % (uint32_t)a.Hkv;
-    const int b = id / (uint32_t)a.Hkv;
+    __shared__ int sh_rank[kMaxRankedChunks + 1];
+    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
     const int hq0 = hk * gt;
-
-    int64_t L = a.N;
-    if (a.valid_len) {
-        L = a.valid_len[b];
-        L = L < 0 ? 0 : (L > a.N ? a.N : L);
-    }
-    int64_t lo, hi;
-    if (a.bounds) {
-        lo = a.bounds[chunk];
-        hi = a.bounds[chunk + 1];
-        lo = lo < 0 ? 0 : (lo > L ? L : lo);
-        hi = hi < lo ? lo : (hi > L ? L : hi);
-    } else {
-        lo = (int64_t)chunk * a.t;
-        lo = lo > L ? L : lo;
-        hi = lo + a.t;
-        hi = hi > L ? L : hi;
-    }
-    const int n = (int)(hi - lo);
+    const int64_t lo = cr.lo;
+    const int n = cr.n;
 
     const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
     if (n <= 0) {   // empty chunk: the identity of the merge
