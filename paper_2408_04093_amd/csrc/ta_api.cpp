@@ -62,7 +62,8 @@ int device_compute_units() {
 // when a chunk would exceed kLongChunk keys.  If there are more (batch, kv
 // head) groups than CUs, or the batch is ragged (lengths live on the device
 // and are unknown here), the work is cut fine enough (>= 8 workgroups per CU,
-// chunks of kRaggedChunk keys) for the hardware dispatcher to balance it.
+// or chunks of kRaggedChunk keys: 4096 measured best on the ragged config, in
+// chunk-major launch order) for the hardware dispatcher to balance it.
 //
 // VALU kernel (fp32 or d = 64): rounds of CUs x resident workgroups, chunks
 // near 4096 keys.
@@ -73,7 +74,7 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     const int64_t groups = (int64_t)p->B * p->Hkv * (g / gt);
     int64_t P;
     if (use_mfma_path(p->qkv_dtype, p->d)) {
-        constexpr int64_t kLongChunk = 32768, kRaggedChunk = 1024, kBalancedChunk = 2048;
+        constexpr int64_t kLongChunk = 32768, kRaggedChunk = 4096, kBalancedChunk = 2048;
         const int64_t per_round = cus / groups;
         if (p->valid_len) {
             P = (p->N + kRaggedChunk - 1) / kRaggedChunk;

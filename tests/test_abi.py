@@ -68,6 +68,7 @@ def test_workspace_and_chunk_heuristic(lib):
     p = llama_problem()
     P = ta.ta_suggest_chunks(p)
     assert 32 <= P <= 512
+    assert (p.B * p.Hkv * P) % 256 == 0       # whole rounds of one workgroup per compute unit
     assert ta.ta_workspace_bytes(p, P) >= 32 * P * 130 * 4
     assert ta.ta_workspace_bytes(p, P) % 256 == 0
     assert ta.ta_workspace_bytes(p, 0) == 0

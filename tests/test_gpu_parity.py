@@ -289,6 +289,72 @@ def test_errors_surface_as_exceptions_on_the_gpu_too():
         ta.decode_partial(w.q, w.K, w.V, float("inf"), P=2)
 
 
+def test_combine_many_partials_spans_several_weight_tiles():
+    """P = 2500 > the 1024 weights staged in LDS at a time."""
+    g = torch.Generator().manual_seed(9)
+    B, Hq, P, d = 1, 3, 2500, 64
+    pm = (torch.randn((B, Hq, P), generator=g) * 5).float()
+    pl = (torch.rand((B, Hq, P), generator=g) + 0.1).float()
+    po = torch.randn((B, Hq, P, d), generator=g).float() * pl[..., None]
+    pl[0, 1, 5::7] = 0; pm[0, 1, 5::7] = -math.inf; po[0, 1, 5::7] = 0
+    out, lse = ta.tree_combine(pm.cuda(), pl.cuda(), po.cuda(), ta.TA_F32)
+    torch.cuda.synchronize()
+    for h in range(Hq):
+        ro, rl = oracle.combine(pm[0, h].numpy(), pl[0, h].numpy(), po[0, h].numpy())
+        assert row_rel_l2(out[0, h].cpu().numpy(), ro) <= 5e-6
+        assert abs(lse[0, h].item() - rl) <= 1e-5
+
+
+def test_long_chunk_table_beyond_the_ranked_limit():
+    """P = 300 unequal chunks (> 256: visited in table order instead of largest first), g = 16."""
+    w = W.make_qkv(1, 16, 1, 128, 9000, torch.bfloat16, seed=31, device="cuda")
+    bounds = W.random_bounds(9000, 300, seed=5).cuda()
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=300, chunk_bounds=bounds)
+    out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+    torch.cuda.synchronize()
+    ref = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+
+
+@pytest.mark.parametrize("dt,d", [("bf16", 64), ("f32", 64), ("f32", 128)])
+def test_ragged_lengths_on_the_valu_kernels(dt, d):
+    dtype = torch.bfloat16 if dt == "bf16" else torch.float32
+    w = W.make_qkv(4, 8, 2, d, 900, dtype, seed=17, device="cuda")
+    w.valid_len = torch.tensor([900, 0, 257, 31], dtype=torch.int32, device="cuda")
+    check(w)
+    bounds = torch.tensor([0, 10, 10, 300, 640, 900], dtype=torch.int64, device="cuda")
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=5, valid_len=w.valid_len, chunk_bounds=bounds)
+    out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+    torch.cuda.synchronize()
+    ref = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref[0]) <= (TOL_BF16_F32OUT if dt == "bf16" else TOL_F32)
+    assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+
+
+def test_kv_views_into_a_larger_cache_allocation():
+    """K/V are the first 700 positions of a cache allocated for 1024 (head stride > N*d)."""
+    B, Hq, Hkv, d = 2, 8, 2, 128
+    big = W.make_qkv(B, Hq, Hkv, d, 1024, torch.bfloat16, seed=41, device="cuda")
+    K, V = big.K[:, :, :700], big.V[:, :, :700]
+    assert not K.is_contiguous()
+    out, lse = ta.decode(big.q, K, V, big.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
+    ref = oracle.decode(big.q.cpu(), K.cpu().contiguous(), V.cpu().contiguous(), big.scale)
+    assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+
+
+def test_bf16_peaked_scores_and_negative_scale():
+    """|score| up to ~60 in bf16 (running-max rescale path) and a negative scale."""
+    w = W.make_qkv(1, 8, 2, 128, 3000, torch.bfloat16, seed=23, device="cuda", q_mult=6.0)
+    ref = oracle_of(w)
+    assert np.abs(ref[1]).max() > 15
+    check(w, ref)
+    w.scale = -w.scale
+    check(w)
+
+
 # ------------------------------------------------------------------ full-size configs, bench launch shape
 def test_config1_llama_128k_full():
     w = W.llama128k(device="cuda")
