@@ -28,6 +28,7 @@ LLC_BYTES = 256 << 20      # Infinity Cache
 
 
 def build_workload(name, device, copy):
+    import torch
     import ta_workloads as W
     if name == "llama128k":
         return W.llama128k(device=device, seed_offset=copy)
@@ -37,6 +38,13 @@ def build_workload(name, device, copy):
         return W.ragged(device=device)
     if name == "combine":
         return W.combine_stress(device=device)
+    if name in ("shard80k", "shard40k"):
+        w = W.paper_shard(N=80000 if name == "shard80k" else 40000, device=device)
+        if copy:   # distinct values per rotating copy
+            g = torch.Generator(device=device).manual_seed(W.BASE_SEED + 5 + 1000 * copy)
+            w.K = torch.randn(w.K.shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+            w.V = torch.randn(w.V.shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+        return w
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -188,7 +196,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the 1M-key workload that the default run reports next to the 128k one")

@@ -138,6 +138,80 @@ int ta_oracle_decode(int B, int Hq, int Hkv, int d, int64_t N,
     return fail ? -1 : 0;
 }
 
+/*
+ * Several query tokens at once with causal masking among them (Appendix C.1,
+ * causal energy F_tot = sum_i log sum_{a <= i} exp(q_i.k_a + zeta_i.v_a)):
+ * the cache of sequence b holds L = valid_len[b] keys, the last Sq of which
+ * belong to the Sq query tokens themselves; query token t (0-based) sees keys
+ * 0 .. L - Sq + t, i.e. L - Sq + t + 1 of them (none if that is <= 0).
+ *   q [B,Sq,Hq,d], K,V [B,Hkv,N,d];  out [B,Sq,Hq,d], lse [B,Sq,Hq] in double.
+ * Each (b, t, h) is the single-query definition above on its own prefix.
+ */
+int ta_oracle_decode_causal(int B, int Sq, int Hq, int Hkv, int d, int64_t N,
+                            const void *q, const void *K, const void *V, int dtype,
+                            double scale, const int32_t *valid_len,
+                            double *out, double *lse, int nthreads)
+{
+    if (B < 0 || Sq <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || N < 0 || Hq % Hkv != 0) return -1;
+    if (dtype < TAO_BF16 || dtype > TAO_F64) return -1;
+    const int g = Hq / Hkv;
+    const int nprob = B * Sq * Hq;
+    int fail = 0;
+#ifdef _OPENMP
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+#endif
+    for (int pidx = 0; pidx < nprob; ++pidx) {
+        const int b = pidx / (Sq * Hq), t = (pidx / Hq) % Sq, hq = pidx % Hq, hk = hq / g;
+        int64_t L = valid_len ? (int64_t)valid_len[b] : N;
+        if (L > N) L = N;
+        if (L < 0) L = 0;
+        int64_t Lt = L - Sq + t + 1;          /* keys visible to token t */
+        if (Lt < 0) Lt = 0;
+        double *s_buf = (double *)malloc(sizeof(double) * (size_t)(Lt > 0 ? Lt : 1));
+        if (!s_buf) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            fail = 1;
+            continue;
+        }
+        decode_one(q, (((int64_t)b * Sq + t) * Hq + hq) * d, K, V,
+                   ((int64_t)b * Hkv + hk) * N * d, dtype, d, Lt, scale,
+                   out + (int64_t)pidx * d, lse + pidx, s_buf);
+        free(s_buf);
+    }
+    return fail ? -1 : 0;
+}
+
+/*
+ * Causal total energy of Appendix C.1 for one head and Sq query tokens:
+ *     F_tot(zeta) = sum_t log sum_{a < L - Sq + t + 1} exp(scale q_t.k_a + zeta_t.v_a).
+ * q [Sq,d], K,V [L,d], zeta [Sq,d] (double).  Every token must see >= 1 key.
+ */
+double ta_oracle_energy_causal(int d, int64_t L, int Sq, const void *q, const void *K,
+                               const void *V, int dtype, double scale, const double *zeta)
+{
+    double total = 0.0;
+    for (int t = 0; t < Sq; ++t) {
+        const int64_t Lt = L - Sq + t + 1;
+        if (Lt <= 0) return NAN;
+        double m = -INFINITY, acc = 0.0;
+        double *r = (double *)malloc(sizeof(double) * (size_t)Lt);
+        if (!r) return NAN;
+        for (int64_t a = 0; a < Lt; ++a) {
+            double zv = 0.0;
+            for (int c = 0; c < d; ++c) zv += zeta[(size_t)t * d + c] * widen(V, dtype, a * d + c);
+            r[a] = score(q, (int64_t)t * d, K, a * d, dtype, d, scale) + zv;
+            if (r[a] > m) m = r[a];
+        }
+        for (int64_t a = 0; a < Lt; ++a) acc += exp(r[a] - m);
+        free(r);
+        total += m + log(acc);
+    }
+    return total;
+}
+
 int ta_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -28,6 +28,11 @@ def _load():
                                      c_dbl, vp, vp, vp, c_int]
     lib.ta_oracle_decode.restype = c_int
     lib.ta_oracle_max_threads.restype = c_int
+    lib.ta_oracle_decode_causal.argtypes = [c_int, c_int, c_int, c_int, c_int, c_i64, vp, vp, vp, c_int,
+                                            c_dbl, vp, vp, vp, c_int]
+    lib.ta_oracle_decode_causal.restype = c_int
+    lib.ta_oracle_energy_causal.argtypes = [c_int, c_i64, c_int, vp, vp, vp, c_int, c_dbl, vp]
+    lib.ta_oracle_energy_causal.restype = c_dbl
     lib.ta_oracle_partial.argtypes = [c_int, vp, vp, vp, c_int, c_dbl, c_i64, c_i64, vp, vp, vp]
     lib.ta_oracle_partial.restype = c_int
     lib.ta_oracle_combine.argtypes = [c_int, c_int, vp, vp, vp, c_int, vp, c_int, vp, vp]
@@ -92,6 +97,44 @@ def decode(q, K, V, scale, valid_len=None, nthreads=None):
     if rc:
         raise RuntimeError("ta_oracle_decode failed")
     return out, lse
+
+
+def decode_causal(q, K, V, scale, valid_len=None, nthreads=None):
+    """q [B,Sq,Hq,d], K,V [B,Hkv,N,d]; the last Sq cached keys are the query tokens' own,
+    token t sees keys 0..L-Sq+t -> (out [B,Sq,Hq,d] f64, lse [B,Sq,Hq] f64)."""
+    lib = _load()
+    q, K, V = (as_oracle_array(a) for a in (q, K, V))
+    dt = _same_dtype(q, K, V)
+    B, Sq, Hq, d = q.shape
+    Bk, Hkv, N, dk = K.shape
+    if (Bk, dk) != (B, d) or V.shape != K.shape or Hq % Hkv:
+        raise ValueError("shape mismatch")
+    vl = None
+    if valid_len is not None:
+        vl = np.ascontiguousarray(np.asarray(valid_len, dtype=np.int32))
+        if vl.shape != (B,):
+            raise ValueError("valid_len must be [B]")
+    out = np.empty((B, Sq, Hq, d), np.float64)
+    lse = np.empty((B, Sq, Hq), np.float64)
+    nt = nthreads if nthreads is not None else max_threads()
+    rc = lib.ta_oracle_decode_causal(B, Sq, Hq, Hkv, d, N, _ptr(q), _ptr(K), _ptr(V), dt, float(scale),
+                                     _ptr(vl) if vl is not None else None, _ptr(out), _ptr(lse), int(nt))
+    if rc:
+        raise RuntimeError("ta_oracle_decode_causal failed")
+    return out, lse
+
+
+def energy_causal(q, K, V, scale, zeta):
+    """F_tot of Appendix C.1 for one head: q [Sq,d], K,V [L,d], zeta [Sq,d] f64."""
+    lib = _load()
+    q, K, V = (as_oracle_array(a) for a in (q, K, V))
+    dt = _same_dtype(q, K, V)
+    L, d = K.shape
+    Sq = q.shape[0]
+    zeta = np.ascontiguousarray(np.asarray(zeta, dtype=np.float64))
+    if zeta.shape != (Sq, d):
+        raise ValueError("zeta must be [Sq,d]")
+    return float(lib.ta_oracle_energy_causal(d, L, Sq, _ptr(q), _ptr(K), _ptr(V), dt, float(scale), _ptr(zeta)))
 
 
 def partial(q, K, V, scale, lo, hi):

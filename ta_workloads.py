@@ -16,6 +16,10 @@ Recipes (config index k uses seed 20240804 + k):
   4 combine   B=4 Hq=64 Hkv=8 d=128 N=262144 bf16, N(0,1); chunk bounds = 0, P-1
               distinct cut points uniform on {1..N-1} sorted, N (P=64), shared
               by every (b, h)
+  5 shard     the paper's own micro-benchmark shard: one device's share of its 16-head,
+              d=128, bf16 attention block (Section 6.1): B=1 Hq=Hkv=16, N=80000
+              (640 000 tokens over 8 GPUs, Section 6.3) or N=40000 (5.12 M over 128),
+              N(0,1) with q multiplied by 1/sqrt(128), scale 1 as in the paper
 Every generator takes size overrides so tests can run the same recipe small.
 """
 from dataclasses import dataclass, field
@@ -124,6 +128,14 @@ def million(N=1048576, device="cpu", B=1, Hq=32, Hkv=8, d=128, frac=0.01, offset
 def combine_stress(N=262144, P=64, device="cpu", B=4, Hq=64, Hkv=8, d=128):
     w = make_qkv(B, Hq, Hkv, d, N, torch.bfloat16, BASE_SEED + 4, device, name="combine")
     w.chunk_bounds = random_bounds(N, P, BASE_SEED + 4 + 500).to(device)
+    return w
+
+
+def paper_shard(N=80000, device="cpu"):
+    w = make_qkv(1, 16, 16, 128, N, torch.bfloat16, BASE_SEED + 5, device, scale=1.0, name=f"shard{N}")
+    # with scale 1 and unit-variance q the scores have std ~11 and the softmax is one-hot;
+    # q carries the 1/sqrt(d) instead
+    w.q = (w.q.float() * (128 ** -0.5)).to(torch.bfloat16)
     return w
 
 

@@ -410,3 +410,11 @@ def test_config4_combine_stress_unequal_chunks_full():
     out2, lse2 = gpu_decode(w, ta.TA_F32)
     assert row_rel_l2(out2, ref_out) <= TOL_BF16_F32OUT
     assert lse_err(lse2, ref_lse) <= TOL_LSE
+
+
+@pytest.mark.parametrize("N", [80000, 40000])
+def test_paper_shard_shapes_full(N):
+    """One device's share of the paper's 16-head d=128 block (Sections 6.1, 6.3), scale 1."""
+    w = W.paper_shard(N=N, device="cuda")
+    assert w.shape == (1, 16, 16, 128, N) and w.scale == 1.0
+    check(w)

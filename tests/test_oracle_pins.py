@@ -358,3 +358,61 @@ def test_torch_bf16_tensor_conversion_is_bit_exact():
     assert a.dtype == np.uint16
     back = (a.astype(np.uint32) << 16).view(np.float32)
     np.testing.assert_array_equal(back, t.float().numpy())
+
+
+# ---------------------------------------------------------------- several query tokens, causal (Appendix C.1)
+def test_causal_multi_token_equals_single_token_on_each_prefix():
+    """Token t of Sq sees keys 0..L-Sq+t: the single-token result with that valid length."""
+    B, Sq, Hq, Hkv, d, N = 2, 5, 4, 2, 8, 23
+    q = RNG.standard_normal((B, Sq, Hq, d))
+    K = RNG.standard_normal((B, Hkv, N, d))
+    V = RNG.standard_normal((B, Hkv, N, d))
+    vl = [23, 9]
+    out, lse = oracle.decode_causal(q, K, V, 0.6, valid_len=vl)
+    for t in range(Sq):
+        ref, ref_lse = oracle.decode(q[:, t].copy(), K, V, 0.6, valid_len=[L - Sq + t + 1 for L in vl])
+        np.testing.assert_array_equal(out[:, t], ref)
+        np.testing.assert_array_equal(lse[:, t], ref_lse)
+    # and against the library routine on an explicit slice
+    s = 0.6 * (K[1, 1, :9 - 5 + 2 + 1] @ q[1, 2, 3])
+    np.testing.assert_allclose(out[1, 2, 3], scipy.special.softmax(s) @ V[1, 1, :7], atol=1e-13)
+    assert lse[1, 2, 3] == pytest.approx(float(scipy.special.logsumexp(s)), abs=1e-12)
+
+
+def test_causal_single_token_is_plain_decode_and_short_caches_are_defined():
+    q = RNG.standard_normal((1, 1, 2, 4))
+    K = RNG.standard_normal((1, 1, 6, 4))
+    V = RNG.standard_normal((1, 1, 6, 4))
+    a = oracle.decode_causal(q, K, V, 1.0)
+    b = oracle.decode(q[:, 0].copy(), K, V, 1.0)
+    np.testing.assert_array_equal(a[0][:, 0], b[0])
+    # 3 query tokens but only 2 cached keys: token 0 sees nothing, token 1 one key, token 2 both
+    q3 = RNG.standard_normal((1, 3, 2, 4))
+    out, lse = oracle.decode_causal(q3, K, V, 1.0, valid_len=[2])
+    assert not out[0, 0].any() and np.all(lse[0, 0] == -np.inf)
+    np.testing.assert_array_equal(out[0, 1], np.broadcast_to(V[0, 0, 0], (2, 4)))
+    assert np.isfinite(lse[0, 2]).all()
+
+
+def test_causal_output_is_gradient_of_the_total_energy():
+    """d F_tot / d zeta_t at zeta = 0 is the output of token t; F_tot(0) = sum of the lse."""
+    d, L, Sq = 5, 14, 3
+    q = RNG.standard_normal((Sq, d))
+    K = RNG.standard_normal((L, d))
+    V = RNG.standard_normal((L, d))
+    out, lse = oracle.decode_causal(q[None, :, None], K[None, None], V[None, None], 0.7)
+    out, lse = out[0, :, 0], lse[0, :, 0]
+    z0 = np.zeros((Sq, d))
+    assert oracle.energy_causal(q, K, V, 0.7, z0) == pytest.approx(lse.sum(), abs=1e-12)
+    h = 1e-5
+    for t in range(Sq):
+        for c in range(d):
+            e = np.zeros((Sq, d))
+            e[t, c] = h
+            fd = (oracle.energy_causal(q, K, V, 0.7, e) - oracle.energy_causal(q, K, V, 0.7, -e)) / (2 * h)
+            assert fd == pytest.approx(out[t, c], abs=2e-9)
+    # the total energy itself against the library routine
+    zeta = RNG.standard_normal((Sq, d)) * 0.2
+    ref = sum(float(scipy.special.logsumexp(0.7 * (K[:L - Sq + t + 1] @ q[t]) + V[:L - Sq + t + 1] @ zeta[t]))
+              for t in range(Sq))
+    assert oracle.energy_causal(q, K, V, 0.7, zeta) == pytest.approx(ref, abs=1e-12)
