@@ -38,6 +38,10 @@ def build_workload(name, device, copy):
         return W.ragged(device=device)
     if name == "combine":
         return W.combine_stress(device=device)
+    if name == "llama128k_sq4":
+        # 4 query tokens (speculative decoding) on the llama128k shape: 4 tokens x 4 heads = 16 MFMA rows
+        return W.make_multi(1, 4, 32, 8, 128, 131072, torch.bfloat16, W.BASE_SEED + 6 + 1000 * copy, device,
+                            name="llama128k_sq4")
     if name in ("shard80k", "shard40k"):
         w = W.paper_shard(N=80000 if name == "shard80k" else 40000, device=device)
         if copy:   # distinct values per rotating copy
@@ -51,7 +55,8 @@ def build_workload(name, device, copy):
 def algorithmic_bytes(w):
     """Valid K and V rows once each, plus q in and out + lse out (bf16 out)."""
     B, Hq, Hkv, d, N = w.shape
-    return w.kv_bytes() + B * Hq * d * w.q.element_size() + B * Hq * (d * 2 + 4)
+    rows = w.q.numel() // d                      # (batch, token, head) rows
+    return w.kv_bytes() + rows * d * w.q.element_size() + rows * (d * 2 + 4)
 
 
 def read_traffic(workload):
@@ -87,10 +92,11 @@ def run_workload(name, steps, warmup, cpu_baseline):
     P = bounds.numel() - 1 if bounds is not None else ta.ta_suggest_chunks(probs[0])
     wbytes = ta.ta_workspace_bytes(probs[0], P)
     workspace = torch.empty(wbytes, dtype=torch.uint8, device=dev)
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device=dev)
-    lse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+    Sq = w0.q.shape[1] if w0.q.dim() == 4 else 1
+    out = torch.empty(tuple(w0.q.shape), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty(tuple(w0.q.shape[:-1]), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
-    bhp = B * Hq * P
+    bhp = B * Sq * Hq * P
     part_o = workspace[:bhp * d * 4].view(torch.float32)
     part_m = workspace[bhp * d * 4:bhp * (d + 1) * 4].view(torch.float32)
     part_l = workspace[bhp * (d + 1) * 4:bhp * (d + 2) * 4].view(torch.float32)
@@ -106,7 +112,7 @@ def run_workload(name, steps, warmup, cpu_baseline):
     def step(i):
         if bounds is not None:
             partial_only(i)
-            rc = ta.ta_tree_combine(B, Hq, d, P, part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(),
+            rc = ta.ta_tree_combine(B, Sq * Hq, d, P, part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(),
                                     out.data_ptr(), ta.TA_BF16, lse.data_ptr(), stream)
             if rc:
                 raise ta.TAError(rc, "ta_tree_combine")
@@ -149,7 +155,7 @@ def run_workload(name, steps, warmup, cpu_baseline):
         "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w0.q.dtype == torch.bfloat16 else "f32", "data": "synthetic",
-        "config": {"workload": name, "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
+        "config": {"workload": name, "B": B, "Sq": Sq, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
                    "chunks_P": P, "chunking": "unequal table" if bounds is not None else "equal",
                    "kv_buffers_rotated": n_copies,
                    "algorithmic_bytes_per_step": alg},
@@ -165,23 +171,24 @@ def run_workload(name, steps, warmup, cpu_baseline):
         q_c, K_c, V_c = w.q.cpu(), w.K.cpu(), w.V.cpu()
         vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
         # bounded sample: whole workload if it is <= ~2 G multiply-adds, else a prefix of the heads
-        macs = 2.0 * Hq * d * (float(w.valid_len.sum()) if w.valid_len is not None else B * N)
+        macs = 2.0 * Sq * Hq * d * (float(w.valid_len.sum()) if w.valid_len is not None else B * N)
         hq_s = Hq if macs <= 2.5e10 else max(Hq // Hkv, int(Hq * 2.5e10 / macs) // (Hq // Hkv) * (Hq // Hkv))
         hk_s = hq_s // (Hq // Hkv)
         nthreads = oracle.max_threads()
-        q_s, K_s, V_s = q_c[:, :hq_s].contiguous(), K_c[:, :hk_s].contiguous(), V_c[:, :hk_s].contiguous()
+        q_s, K_s, V_s = q_c[..., :hq_s, :].contiguous(), K_c[:, :hk_s].contiguous(), V_c[:, :hk_s].contiguous()
+        oracle_fn = oracle.decode_causal if Sq > 1 else oracle.decode
         passes, dt = 0, 0.0
         while passes < 3 and dt < 20.0:             # a few passes for a stable figure, bounded in time
             t0 = time.perf_counter()
-            ref_out, ref_lse = oracle.decode(q_s, K_s, V_s, w.scale, vl, nthreads)
+            ref_out, ref_lse = oracle_fn(q_s, K_s, V_s, w.scale, vl, nthreads)
             dt += time.perf_counter() - t0
             passes += 1
         dt /= passes
         sample_bytes = w.kv_bytes() * hk_s / Hkv
-        got = out[:, :hq_s].float().cpu().numpy().astype(np.float64)
+        got = out[..., :hq_s, :].float().cpu().numpy().astype(np.float64)
         rel = float((np.linalg.norm(got - ref_out, axis=-1) /
                      np.maximum(np.linalg.norm(ref_out, axis=-1), 1e-300)).max())
-        dl = float(np.abs(lse[:, :hq_s].cpu().numpy() - ref_lse).max())
+        dl = float(np.abs(lse[..., :hq_s].cpu().numpy() - ref_lse).max())
         result["cpu_baseline"] = {
             "value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
             "seconds": round(dt, 3),
@@ -196,7 +203,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the 1M-key workload that the default run reports next to the 128k one")

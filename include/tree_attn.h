@@ -34,6 +34,18 @@
  *     part_o [B,Hq,P,d], contiguous.  The paper's per-device (o, lse) are
  *     o / l and m + log l.  An empty chunk stores (-inf, 0, 0).
  *   - NaN or Inf in q, K or V: behaviour undefined.
+ *   - Several query tokens (Sq > 1; speculative decoding, the tail of a chunked
+ *     prefill): the paper's causal energy F_tot = sum_i log sum_{a <= i} exp(..)
+ *     (Appendix C.1) restricted to the last Sq positions.  The cache of
+ *     sequence b already holds the Sq new tokens' keys and values as its last
+ *     Sq valid positions; query token t (0-based) attends to keys
+ *     0 .. valid_len[b] - Sq + t.  A token that sees no key gets out = 0,
+ *     lse = -inf.  Shapes gain a token axis: q and out [B,Sq,Hq,d],
+ *     lse [B,Sq,Hq], partials [B,Sq,Hq,P] and [B,Sq,Hq,P,d]; for
+ *     ta_tree_combine pass Sq*Hq as Hq.  All tokens and heads of a KV group
+ *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 16; beyond that the
+ *     tokens are processed in slices of floor(16 / (Hq/Hkv)), each slice
+ *     reading K/V once.  Sq > 1 needs bf16 inputs and d = 128.
  */
 #ifndef TREE_ATTN_H
 #define TREE_ATTN_H
@@ -60,7 +72,7 @@ typedef enum { TA_BF16 = 0, TA_F32 = 1 } ta_dtype;
 
 /*
  * One decode-attention problem.  Read on the host only.
- *   q   [B,Hq,d]       contiguous
+ *   q   [B,Hq,d]       contiguous  ([B,Sq,Hq,d] when Sq > 1)
  *   K,V [B,Hkv,N,d]    innermost stride 1; the other strides are given in
  *                      ELEMENTS and must keep every row 16-byte aligned
  *                      (stride_n >= d).  A whole [N,d] head slice must span
@@ -79,6 +91,9 @@ typedef struct ta_problem {
     int32_t out_dtype;                           /* ta_dtype of `out` (ta_decode only) */
     float scale;                                 /* finite; multiplies q . k           */
     const int32_t *valid_len;                    /* device int32 [B], or NULL = N      */
+    int32_t Sq;                                  /* query tokens per sequence; 0 or 1 =
+                                                    plain decode (see "Several query
+                                                    tokens" above)                     */
 } ta_problem;
 
 /* Human-readable name of a status code; never NULL; static storage. */
@@ -94,7 +109,7 @@ int32_t ta_suggest_chunks(const ta_problem *p);
 
 /*
  * Bytes of workspace ta_decode needs when it runs with P chunks:
- * B*Hq*P*(d+2) floats, rounded up to 256 bytes.  Returns 0 if the problem
+ * B*Sq*Hq*P*(d+2) floats, rounded up to 256 bytes.  Returns 0 if the problem
  * is invalid or P < 1.
  */
 size_t ta_workspace_bytes(const ta_problem *p, int32_t P);

@@ -30,6 +30,7 @@ class Problem(ctypes.Structure):
         ("qkv_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("scale", ctypes.c_float),
         ("valid_len", ctypes.c_void_p),
+        ("Sq", ctypes.c_int32),
     ]
 
 
@@ -110,8 +111,9 @@ def _stream():
 
 
 def make_problem(q, K, V, scale, valid_len=None, out_dtype=None):
-    """Describe torch tensors q [B,Hq,d], K,V [B,Hkv,N,d] (last dim contiguous)."""
-    B, Hq, d = q.shape
+    """Describe torch tensors q [B,Hq,d] or [B,Sq,Hq,d], K,V [B,Hkv,N,d] (last dim contiguous)."""
+    Sq = q.shape[1] if q.dim() == 4 else 1
+    B, Hq, d = q.shape[0], q.shape[-2], q.shape[-1]
     _, Hkv, N, _ = K.shape
     if not q.is_contiguous() or K.stride(3) != 1 or V.stride(3) != 1:
         raise ValueError("q must be contiguous and K, V must have unit innermost stride")
@@ -125,6 +127,7 @@ def make_problem(q, K, V, scale, valid_len=None, out_dtype=None):
     p.out_dtype = p.qkv_dtype if out_dtype is None else out_dtype
     p.scale = float(scale)
     p.valid_len = valid_len.data_ptr() if valid_len is not None else None
+    p.Sq = Sq
     return p
 
 
@@ -132,10 +135,10 @@ def decode_partial(q, K, V, scale, P, valid_len=None, chunk_bounds=None):
     """-> (part_m [B,Hq,P], part_l [B,Hq,P], part_o [B,Hq,P,d]) fp32 device tensors."""
     import torch
     p = make_problem(q, K, V, scale, valid_len)
-    B, Hq, d = q.shape
-    part_m = torch.empty((B, Hq, P), dtype=torch.float32, device=q.device)
+    lead, d = tuple(q.shape[:-1]), q.shape[-1]          # (B,Hq) or (B,Sq,Hq)
+    part_m = torch.empty(lead + (P,), dtype=torch.float32, device=q.device)
     part_l = torch.empty_like(part_m)
-    part_o = torch.empty((B, Hq, P, d), dtype=torch.float32, device=q.device)
+    part_o = torch.empty(lead + (P, d), dtype=torch.float32, device=q.device)
     rc = ta_decode_partial(p, q.data_ptr(), K.data_ptr(), V.data_ptr(), P,
                            chunk_bounds.data_ptr() if chunk_bounds is not None else None,
                            part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(), _stream())
@@ -145,12 +148,13 @@ def decode_partial(q, K, V, scale, P, valid_len=None, chunk_bounds=None):
 
 
 def tree_combine(part_m, part_l, part_o, out_dtype=TA_F32):
-    """-> (out [B,Hq,d], lse [B,Hq])."""
+    """part_o [B,Hq,P,d] or [B,Sq,Hq,P,d] -> (out [..,d], lse [..]) with the same leading axes."""
     import torch
-    B, Hq, P, d = part_o.shape
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16 if out_dtype == TA_BF16 else torch.float32,
+    lead, P, d = tuple(part_o.shape[:-2]), part_o.shape[-2], part_o.shape[-1]
+    B, Hq = lead[0], int(torch.Size(lead[1:]).numel())
+    out = torch.empty(lead + (d,), dtype=torch.bfloat16 if out_dtype == TA_BF16 else torch.float32,
                       device=part_o.device)
-    lse = torch.empty((B, Hq), dtype=torch.float32, device=part_o.device)
+    lse = torch.empty(lead, dtype=torch.float32, device=part_o.device)
     rc = ta_tree_combine(B, Hq, d, P, part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(),
                          out.data_ptr(), out_dtype, lse.data_ptr(), _stream())
     if rc:
@@ -162,16 +166,16 @@ def decode(q, K, V, scale, valid_len=None, out_dtype=None, workspace=None):
     """-> (out [B,Hq,d], lse [B,Hq]); `workspace` (uint8 device tensor) is reused if given."""
     import torch
     p = make_problem(q, K, V, scale, valid_len, out_dtype)
-    B, Hq, d = q.shape
+    lead, d = tuple(q.shape[:-1]), q.shape[-1]
     need = ta_workspace_bytes(p, ta_suggest_chunks(p))
     if need == 0:
         raise TAError(load().ta_decode(ctypes.byref(p), None, None, None, None, 0, None, None, None),
                       "ta_decode")
     if workspace is None or workspace.numel() < need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16 if p.out_dtype == TA_BF16 else torch.float32,
+    out = torch.empty(lead + (d,), dtype=torch.bfloat16 if p.out_dtype == TA_BF16 else torch.float32,
                       device=q.device)
-    lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    lse = torch.empty(lead, dtype=torch.float32, device=q.device)
     rc = ta_decode(p, q.data_ptr(), K.data_ptr(), V.data_ptr(), workspace.data_ptr(), workspace.numel(),
                    out.data_ptr(), lse.data_ptr(), _stream())
     if rc:

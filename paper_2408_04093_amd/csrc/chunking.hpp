@@ -16,6 +16,7 @@ namespace ta {
 struct ChunkRange {
     int b, hk, slice, chunk;
     int64_t lo;   // first key of the chunk
+    int64_t L;    // valid length of the sequence
     int n;        // number of keys (0 = empty)
 };
 
@@ -79,6 +80,7 @@ __device__ __forceinline__ ChunkRange select_chunk(const PartialArgs &a, int *sh
         hi = hi > L ? L : hi;
     }
     c.lo = lo;
+    c.L = L;
     c.n = (int)(hi - lo);
     return c;
 }

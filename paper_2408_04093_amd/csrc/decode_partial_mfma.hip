@@ -74,34 +74,54 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;     // row group / (column block or head)
-    const int gt = a.g;                         // heads of the group, all in this workgroup
+    const int g = a.g;                          // heads of the group, all in this workgroup
 
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
-    const int hq0 = hk * gt;
     const int64_t lo = cr.lo;
     const int n = cr.n;
 
-    const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
+    // MFMA rows: row = (local token) * g + (head in group); this workgroup owns
+    // query tokens [t0, t0 + ntok) of the Sq (one token in plain decode)
+    const int t0 = cr.slice * a.tq;
+    const int ntok = (a.Sq - t0) < a.tq ? (a.Sq - t0) : a.tq;
+    const int nrows = ntok * g;
+    const int HqV = a.Sq * a.Hq;                // (token, head) pairs per sequence
+    // virtual head of row x: token-major [Sq][Hq]
+    auto vhead = [&](int row) { return (t0 + row / g) * a.Hq + hk * g + row % g; };
+    const int my_row = c < nrows ? c : 0;       // row served by this lane as "head" lane
+    const int my_tok = t0 + my_row / g;
+
     if (n <= 0) {   // empty chunk: the identity of the merge
-        for (int i = tid; i < gt * D; i += kThreads)
-            a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
-        if (tid < gt) {
-            a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
-            a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+        for (int i = tid; i < nrows * D; i += kThreads)
+            a.part_o[(((int64_t)b * HqV + vhead(i / D)) * a.P + chunk) * D + (i % D)] = 0.f;
+        if (tid < nrows) {
+            const int64_t pi = ((int64_t)b * HqV + vhead(tid)) * a.P + chunk;
+            a.part_m[pi] = -__builtin_huge_valf();
+            a.part_l[pi] = 0.f;
         }
         return;
     }
 
-    // Q^T as MFMA B operand: lane (kb = r, head = c) holds q[head][32t + 8r .. +8], zero for padded heads
+    // Causal limit among the query tokens: token t sees keys < L - Sq + 1 + t.
+    // nlim: chunk-relative count of keys this lane's row may use; n_common: keys every row may use.
+    int nlim, n_common;
+    {
+        int64_t lim = cr.L - a.Sq + 1 + my_tok - lo;
+        nlim = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
+        int64_t limc = cr.L - a.Sq + 1 + t0 - lo;
+        n_common = (int)(limc < 0 ? 0 : (limc > n ? n : limc));
+    }
+
+    // Q^T as MFMA B operand: lane (kb = r, row = c) holds q[row][32t + 8r .. +8], zero for padded rows
     bf16x8 qb[4];
     {
-        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + (c < gt ? c : 0)) * D + 8 * r) * 2;
+        const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row)) * D + 8 * r) * 2;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
-            if (c >= gt) raw = v4i{0, 0, 0, 0};
+            if (c >= nrows) raw = v4i{0, 0, 0, 0};
             qb[t] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -115,7 +135,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 
     constexpr int ROWS_ITER = kWaves * kTile;
     const int n_iters = (n + ROWS_ITER - 1) / ROWS_ITER;
-    const int n_full = n / ROWS_ITER;
+    const int n_full = n_common / ROWS_ITER;   // steps in which every key is visible to every row
 
     int trow[8];                // tile row of slot e for this lane
     uint32_t koff[8], voff[8];  // byte offsets in iteration 0
@@ -195,7 +215,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             sv[e] = s[e >> 2][e & 3] * cs;
-            if (masked && it * ROWS_ITER + w * kTile + trow[e] >= n) sv[e] = -__builtin_huge_valf();
+            if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim) sv[e] = -__builtin_huge_valf();
         }
         float mx = sv[0];
 #pragma unroll
@@ -256,38 +276,46 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 
     // ---- merge the waves through LDS (the K staging area is free now)
     __syncthreads();
-    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][gt][D]
+    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][nrows][D]
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int h = 4 * r + i;
-        if (h < gt) {
+        if (h < nrows) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) lds_o[(w * gt + h) * D + 8 * c + j] = acc[j][i];
+            for (int j = 0; j < 8; ++j) lds_o[(w * nrows + h) * D + 8 * c + j] = acc[j][i];
         }
     }
-    if (r == 0 && c < gt) {
+    if (r == 0 && c < nrows) {
         lds_m[w][c] = m_run;
         lds_l[w][c] = l_run;
     }
     __syncthreads();
 
     const int col = tid % D;
-    for (int h = tid / D; h < gt; h += kThreads / D) {
+    for (int h = tid / D; h < nrows; h += kThreads / D) {
         float ms = lds_m[0][h];
 #pragma unroll
         for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
+        const int64_t pidx = ((int64_t)b * HqV + vhead(h)) * a.P + chunk;
+        if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
+            a.part_o[pidx * D + col] = 0.f;
+            if (col == 0) {
+                a.part_m[pidx] = ms;
+                a.part_l[pidx] = 0.f;
+            }
+            continue;
+        }
         float lt = 0.f, ot = 0.f;
 #pragma unroll
         for (int ww = 0; ww < kWaves; ++ww) {
             const float mw = lds_m[ww][h];
             const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
             lt = fmaf(f, lds_l[ww][h], lt);
-            ot = fmaf(f, lds_o[(ww * gt + h) * D + col], ot);
+            ot = fmaf(f, lds_o[(ww * nrows + h) * D + col], ot);
         }
         // natural-log units for the stored max; l and o follow the rounding of the stored value
         const float m_nat = ms * (float)kLn2;
         const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
-        const int64_t pidx = pidx0 + (int64_t)h * a.P;
         a.part_o[pidx * D + col] = ot * fix;
         if (col == 0) {
             a.part_m[pidx] = m_nat;
@@ -299,7 +327,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 }  // namespace
 
 hipError_t launch_decode_partial_mfma(const PartialArgs &a, hipStream_t s) {
-    const int64_t blocks = (int64_t)a.B * a.Hkv * a.P;
+    const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
     hipLaunchKernelGGL(decode_partial_mfma_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }

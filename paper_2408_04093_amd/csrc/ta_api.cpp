@@ -12,6 +12,21 @@ namespace {
 using namespace ta;
 
 inline int elem_bytes(int dt) { return dt == TA_BF16 ? 2 : 4; }
+inline int tokens(const ta_problem *p) { return p->Sq > 1 ? p->Sq : 1; }
+// query tokens per workgroup on the matrix-core kernel: tokens * group heads fill the 16 MFMA rows
+inline int tokens_per_workgroup(const ta_problem *p) {
+    const int tq = 16 / (p->Hq / p->Hkv);
+    return tq < tokens(p) ? tq : tokens(p);
+}
+// independent workgroup groups per chunk index
+inline int64_t launch_groups(const ta_problem *p) {
+    const int g = p->Hq / p->Hkv;
+    if (use_mfma_path(p->qkv_dtype, p->d)) {
+        const int tq = tokens_per_workgroup(p);
+        return (int64_t)p->B * p->Hkv * ((tokens(p) + tq - 1) / tq);
+    }
+    return (int64_t)p->B * p->Hkv * (g / heads_per_workgroup(p->qkv_dtype, p->d, g));
+}
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape / stride / dtype checks common to every entry point that takes a problem.
@@ -35,7 +50,9 @@ ta_status check_problem(const ta_problem *p) {
     // 32-bit byte offsets inside one [N, d] head slice
     const int64_t lim = (int64_t)1 << 32;
     if (p->N * p->k_stride_n * eb >= lim || p->N * p->v_stride_n * eb >= lim) return TA_ERR_UNSUPPORTED;
-    if ((int64_t)p->B * p->Hq >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
+    if (p->Sq < 0 || p->Sq > 4096) return TA_ERR_SHAPE;
+    if (p->Sq > 1 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
+    if ((int64_t)p->B * p->Hq * tokens(p) >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
     return TA_OK;
 }
 
@@ -71,7 +88,7 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     constexpr int64_t kMinChunk = 256;
     const int g = p->Hq / p->Hkv;
     const int gt = heads_per_workgroup(p->qkv_dtype, p->d, g);
-    const int64_t groups = (int64_t)p->B * p->Hkv * (g / gt);
+    const int64_t groups = launch_groups(p);
     int64_t P;
     if (use_mfma_path(p->qkv_dtype, p->d)) {
         constexpr int64_t kLongChunk = 32768, kRaggedChunk = 4096, kBalancedChunk = 2048;
@@ -107,7 +124,7 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
 }
 
 size_t workspace_bytes(const ta_problem *p, int32_t P) {
-    const size_t floats = (size_t)p->B * p->Hq * (size_t)P * (size_t)(p->d + 2);
+    const size_t floats = (size_t)p->B * tokens(p) * p->Hq * (size_t)P * (size_t)(p->d + 2);
     return (floats * sizeof(float) + 255) & ~(size_t)255;
 }
 
@@ -165,7 +182,9 @@ ta_status ta_decode_partial(const ta_problem *p, const void *q, const void *K, c
     a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
     a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
     a.g = p->Hq / p->Hkv;
-    a.slices = a.g / heads_per_workgroup(p->qkv_dtype, p->d, a.g);
+    a.Sq = tokens(p);
+    a.tq = tokens_per_workgroup(p);
+    a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
     a.c = (double)p->scale * kLog2e;
     if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
     const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
@@ -204,13 +223,14 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
 
     // workspace layout: part_o [B,Hq,P,d] | part_m [B,Hq,P] | part_l [B,Hq,P]
-    const size_t bhp = (size_t)p->B * p->Hq * (size_t)P;
+    const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;
     float *part_o = static_cast<float *>(workspace);
     float *part_m = part_o + bhp * p->d;
     float *part_l = part_m + bhp;
     ta_status s2 = ta_decode_partial(p, q, K, V, P, nullptr, part_m, part_l, part_o, stream);
     if (s2 != TA_OK) return s2;
-    return ta_tree_combine(p->B, p->Hq, p->d, P, part_m, part_l, part_o, out, p->out_dtype, lse, stream);
+    return ta_tree_combine(p->B, tokens(p) * p->Hq, p->d, P, part_m, part_l, part_o, out, p->out_dtype, lse,
+                           stream);
 }
 
 }  // extern "C"

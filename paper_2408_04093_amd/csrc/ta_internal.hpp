@@ -22,7 +22,9 @@ struct PartialArgs {
     uint32_t k_row_bytes, v_row_bytes;
     int32_t B, Hq, Hkv, P;
     int32_t g;                  // Hq / Hkv
-    int32_t slices;             // g / heads-per-workgroup
+    int32_t slices;             // VALU kernel: g / heads-per-workgroup; MFMA kernel: token slices
+    int32_t Sq;                 // query tokens per sequence (>= 1)
+    int32_t tq;                 // MFMA kernel: query tokens per workgroup, tq * g <= 16
     double c;                   // scale * log2(e)
 };
 

@@ -43,7 +43,7 @@ class Workload:
 
     @property
     def shape(self):
-        B, Hq, d = self.q.shape
+        B, Hq, d = self.q.shape[0], self.q.shape[-2], self.q.shape[-1]
         _, Hkv, N, _ = self.K.shape
         return B, Hq, Hkv, d, N
 
@@ -87,6 +87,15 @@ def make_qkv(B, Hq, Hkv, d, N, dtype, seed, device="cpu", scale=None, q_mult=1.0
     V = _randn_big((B, Hkv, N, d), dtype, g, device)
     return Workload(name, q, K, V, float(scale if scale is not None else d ** -0.5),
                     meta=dict(seed=seed, q_mult=q_mult))
+
+
+def make_multi(B, Sq, Hq, Hkv, d, N, dtype, seed, device="cpu", scale=None, name="multi"):
+    """Like make_qkv with Sq query tokens per sequence: q [B,Sq,Hq,d]."""
+    g = _gen(seed, device)
+    q = torch.randn((B, Sq, Hq, d), generator=g, device=device, dtype=torch.float32).to(dtype)
+    K = _randn_big((B, Hkv, N, d), dtype, g, device)
+    V = _randn_big((B, Hkv, N, d), dtype, g, device)
+    return Workload(name, q, K, V, float(scale if scale is not None else d ** -0.5), meta=dict(seed=seed, Sq=Sq))
 
 
 def tiny(N=4096, q_mult=1.0, device="cpu", d=64, dtype=torch.float32):

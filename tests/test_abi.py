@@ -53,9 +53,9 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_struct_layout_matches_header():
-    # 4 int32, 7 int64, 2 int32, float (+pad), pointer
-    assert ctypes.sizeof(ta.Problem) == 16 + 56 + 8 + 8 + 8
-    assert ta.Problem.valid_len.offset == 88 and ta.Problem.scale.offset == 80
+    # 4 int32, 7 int64, 2 int32, float (+pad), pointer, int32 (+pad)
+    assert ctypes.sizeof(ta.Problem) == 16 + 56 + 8 + 8 + 8 + 8
+    assert ta.Problem.valid_len.offset == 88 and ta.Problem.scale.offset == 80 and ta.Problem.Sq.offset == 96
 
 
 def test_status_strings(lib):
@@ -76,6 +76,10 @@ def test_workspace_and_chunk_heuristic(lib):
     assert ta.ta_suggest_chunks(p) == 1
     p.d = 96
     assert ta.ta_suggest_chunks(p) == 0 and ta.ta_workspace_bytes(p, 4) == 0
+    p = llama_problem()
+    p.Sq = 8                # 8 tokens x group of 4 = 32 rows -> two token slices, partials for 8 x 32 heads
+    assert ta.ta_workspace_bytes(p, 16) >= 8 * 32 * 16 * 130 * 4
+    assert (p.B * p.Hkv * 2 * ta.ta_suggest_chunks(p)) % 256 == 0
 
 
 @pytest.mark.parametrize("mutate,code", [
@@ -88,6 +92,8 @@ def test_workspace_and_chunk_heuristic(lib):
     (lambda p: setattr(p, "v_stride_n", 64), 2),     # rows overlap
     (lambda p: setattr(p, "scale", float("nan")), 2),
     (lambda p: setattr(p, "N", 1 << 25), 6),         # head slice >= 4 GiB
+    (lambda p: setattr(p, "Sq", -1), 2),
+    (lambda p: (setattr(p, "Sq", 4), setattr(p, "qkv_dtype", 1)), 6),   # several tokens need bf16, d = 128
 ])
 def test_bad_problems_are_refused_before_launch(lib, mutate, code):
     p = llama_problem()

@@ -418,3 +418,61 @@ def test_paper_shard_shapes_full(N):
     w = W.paper_shard(N=N, device="cuda")
     assert w.shape == (1, 16, 16, 128, N) and w.scale == 1.0
     check(w)
+
+
+# ------------------------------------------------------------------ several query tokens, causal among them
+def check_multi(w):
+    vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
+    ref_out, ref_lse = oracle.decode_causal(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    out_b, lse_b = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_BF16)
+    torch.cuda.synchronize()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    assert out.shape == ref_out.shape and np.isfinite(out).all()
+    assert row_rel_l2(out, ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse, ref_lse) <= TOL_LSE
+    np.testing.assert_array_equal(lse_b.cpu().numpy(), lse)
+    check_bf16_output(out_b.float().cpu().numpy(), out, ref_out)
+    return ref_out, ref_lse
+
+
+@pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [
+    (1, 2, 4, 1, 300), (2, 4, 8, 2, 1000), (1, 16, 1, 1, 777), (1, 3, 8, 1, 513),
+    (1, 8, 32, 8, 4099), (2, 5, 16, 16, 129), (1, 7, 12, 2, 2048), (1, 4, 16, 1, 640)])
+def test_multi_token_causal_decode(B, Sq, Hq, Hkv, N):
+    w = W.make_multi(B, Sq, Hq, Hkv, 128, N, torch.bfloat16, seed=77 + Sq + N, device="cuda")
+    check_multi(w)
+    if B > 1:
+        w.valid_len = torch.tensor([N, max(1, N // 3)][:B], dtype=torch.int32, device="cuda")
+        check_multi(w)
+
+
+def test_multi_token_more_tokens_than_keys_and_chunks_inside_the_new_tokens():
+    # 6 query tokens, caches of 3 and 0 keys: early tokens see nothing
+    w = W.make_multi(2, 6, 4, 1, 128, 64, torch.bfloat16, seed=5, device="cuda")
+    w.valid_len = torch.tensor([3, 0], dtype=torch.int32, device="cuda")
+    ref_out, ref_lse = check_multi(w)
+    assert np.isneginf(ref_lse[0, :3]).all() and np.isfinite(ref_lse[0, 3:]).all() and np.isneginf(ref_lse[1]).all()
+    # 50 chunks of 2 keys over 100 keys with 16 query tokens: the last 8 chunks lie inside the new tokens
+    w = W.make_multi(1, 16, 1, 1, 128, 100, torch.bfloat16, seed=6, device="cuda")
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=50)
+    assert pm.shape == (1, 16, 1, 50) and po.shape == (1, 16, 1, 50, 128)
+    assert pl[0, 0, 0, 43:].sum().item() == 0 and pl[0, 15, 0, 49].item() > 0     # token 0 sees keys 0..84 only
+    out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle.decode_causal(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale)
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+
+
+def test_multi_token_needs_bf16_d128():
+    w = W.make_multi(1, 2, 4, 1, 64, 100, torch.bfloat16, seed=1, device="cuda")
+    with pytest.raises(ta.TAError) as e:
+        ta.decode(w.q, w.K, w.V, w.scale)
+    assert e.value.code == 6
+
+
+def test_multi_token_llama_shape_full():
+    """Llama head shape, 4 draft tokens (16 MFMA rows) over 128k keys: one pass over K/V."""
+    w = W.make_multi(1, 4, 32, 8, 128, 131072, torch.bfloat16, seed=W.BASE_SEED + 6, device="cuda")
+    check_multi(w)
