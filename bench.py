@@ -71,7 +71,7 @@ def read_traffic(workload):
     return None
 
 
-def run_workload(name, steps, warmup, cpu_baseline):
+def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
     """Time `steps` steps of the hot path on workload `name`; returns the result dict."""
     import numpy as np
     import torch
@@ -126,11 +126,31 @@ def run_workload(name, steps, warmup, cpu_baseline):
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if use_graph:
+        # one HIP graph holding n_copies consecutive steps (one per rotating input set), replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            stream = torch.cuda.current_stream().cuda_stream
+            for i in range(n_copies):
+                step(i)
+        stream = torch.cuda.current_stream().cuda_stream
+        reps = max(1, steps // n_copies)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        steps = reps * n_copies
+    else:
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
     gbps = alg / (ms_per_step * 1e-3) / 1e9
 
@@ -157,7 +177,7 @@ def run_workload(name, steps, warmup, cpu_baseline):
         "dtype": "bf16" if w0.q.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": name, "B": B, "Sq": Sq, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
                    "chunks_P": P, "chunking": "unequal table" if bounds is not None else "equal",
-                   "kv_buffers_rotated": n_copies,
+                   "kv_buffers_rotated": n_copies, "launch": "hip graph replay" if use_graph else "eager",
                    "algorithmic_bytes_per_step": alg},
         "roofline": {"kernel": "decode_partial", "bound": "hbm", "achieved": round(ach, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
@@ -205,6 +225,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="launch the timed steps by replaying a captured HIP graph instead of eagerly")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the 1M-key workload that the default run reports next to the 128k one")
     args = ap.parse_args()
@@ -221,7 +243,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.graph)
     if args.workload == "llama128k" and not args.no_extra:
         # the metric is quoted at 128k and at 1M keys: report the second size in the same line
         torch.cuda.empty_cache()

@@ -476,3 +476,44 @@ def test_multi_token_llama_shape_full():
     """Llama head shape, 4 draft tokens (16 MFMA rows) over 128k keys: one pass over K/V."""
     w = W.make_multi(1, 4, 32, 8, 128, 131072, torch.bfloat16, seed=W.BASE_SEED + 6, device="cuda")
     check_multi(w)
+
+
+def test_graph_capture_and_replay():
+    """The library neither allocates nor synchronises, so a step can be captured in a HIP graph.
+    Replayed several times with new inputs written into the captured buffers in between."""
+    w = W.make_qkv(2, 8, 2, 128, 3000, torch.bfloat16, seed=61, device="cuda")
+    w.valid_len = torch.tensor([3000, 1234], dtype=torch.int32, device="cuda")
+    p = ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    P = ta.ta_suggest_chunks(p)
+    nbytes = ta.ta_workspace_bytes(p, P)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((2, 8), dtype=torch.float32, device="cuda")
+
+    def launch():
+        rc = ta.ta_decode(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), ws.data_ptr(), nbytes,
+                          out.data_ptr(), lse.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        launch()                                   # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(s)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch()
+    for rep in range(3):
+        g = torch.Generator(device="cuda").manual_seed(100 + rep)
+        w.q.copy_(torch.randn(w.q.shape, generator=g, device="cuda").to(torch.bfloat16))
+        w.K.copy_(torch.randn(w.K.shape, generator=g, device="cuda").to(torch.bfloat16))
+        w.valid_len.copy_(torch.tensor([3000 - 7 * rep, 1234 + 100 * rep], dtype=torch.int32))
+        out.zero_(); lse.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle_of(w)
+        assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
+        assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+        eager = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+        torch.cuda.synchronize()
+        assert torch.equal(eager[0], out) and torch.equal(eager[1], lse)
