@@ -71,7 +71,7 @@ def read_traffic(workload):
     return None
 
 
-def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
+def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"):
     """Time `steps` steps of the hot path on workload `name`; returns the result dict."""
     import numpy as np
     import torch
@@ -85,6 +85,10 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
     ws = [w0] + [build_workload(name, dev, c) for c in range(1, n_copies)]
     B, Hq, Hkv, d, N = w0.shape
     alg = algorithmic_bytes(w0)
+    if op == "energy":
+        alg -= w0.kv_bytes() // 2          # V is not read
+    elif op == "two_pass":
+        alg += w0.kv_bytes() // 2          # K is read twice
 
     probs = [ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_BF16) for w in ws]
     # the "combine" workload fixes its own P unequal chunks; the others use the library's choice
@@ -110,6 +114,17 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
             raise ta.TAError(rc, "ta_decode_partial")
 
     def step(i):
+        if op != "decode":
+            w, p = ws[i % n_copies], probs[i % n_copies]
+            if op == "energy":       # Algorithm 1: lse only, K is the only stream
+                rc = ta.ta_energy(p, w.q.data_ptr(), w.K.data_ptr(), workspace.data_ptr(), wbytes,
+                                  lse.data_ptr(), stream)
+            else:                    # Algorithms 1 + 2: K streamed twice, V once
+                rc = ta.ta_decode_two_pass(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(),
+                                           workspace.data_ptr(), wbytes, out.data_ptr(), lse.data_ptr(), stream)
+            if rc:
+                raise ta.TAError(rc, "ta_" + op)
+            return
         if bounds is not None:
             partial_only(i)
             rc = ta.ta_tree_combine(B, Sq * Hq, d, P, part_m.data_ptr(), part_l.data_ptr(), part_o.data_ptr(),
@@ -167,6 +182,10 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
     us_partial = ev0.elapsed_time(ev1) * 1e3 / steps
     ach = alg / (us_partial * 1e-6) / 1e9
     tr = read_traffic(name)
+    kernel_name = "decode_partial"
+    if op != "decode":
+        # the energy / gradient passes are the same streaming kernel in another mode: report the whole step
+        kernel_name, us_partial, ach, tr = f"{op}: streaming passes + combine", ms_per_step * 1e3, gbps, None
 
     result = {
         "metric": "decode_attention_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
@@ -175,11 +194,11 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False):
         "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w0.q.dtype == torch.bfloat16 else "f32", "data": "synthetic",
-        "config": {"workload": name, "B": B, "Sq": Sq, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
+        "config": {"workload": name, "op": op, "B": B, "Sq": Sq, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N,
                    "chunks_P": P, "chunking": "unequal table" if bounds is not None else "equal",
                    "kv_buffers_rotated": n_copies, "launch": "hip graph replay" if use_graph else "eager",
                    "algorithmic_bytes_per_step": alg},
-        "roofline": {"kernel": "decode_partial", "bound": "hbm", "achieved": round(ach, 1),
+        "roofline": {"kernel": kernel_name, "bound": "hbm", "achieved": round(ach, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4),
                      "us_per_launch": round(us_partial, 2),
                      "traffic": tr},
@@ -225,6 +244,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
+                    help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "
+                         "two_pass = ta_decode_two_pass (Algorithms 1 + 2)")
     ap.add_argument("--graph", action="store_true",
                     help="launch the timed steps by replaying a captured HIP graph instead of eagerly")
     ap.add_argument("--no-extra", action="store_true",
@@ -243,8 +265,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.graph)
-    if args.workload == "llama128k" and not args.no_extra:
+    result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline and args.op == "decode",
+                          args.graph, args.op)
+    if args.workload == "llama128k" and not args.no_extra and args.op == "decode":
         # the metric is quoted at 128k and at 1M keys: report the second size in the same line
         torch.cuda.empty_cache()
         m = run_workload("million", max(10, args.steps // 2), max(3, args.warmup // 4), False)

@@ -158,6 +158,31 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
                     void *workspace, size_t workspace_bytes,
                     void *out, float *lse, void *stream);
 
+/*
+ * The energy alone: lse[b,(t,)h] = F(0) = logsumexp_a(scale q.k_a), Algorithm 1
+ * ("Single Query Energy Forward") with the max and logsumexp reductions fused
+ * into one (m, l) reduction.  zeta is zero and never materialised, so V is not
+ * an argument and only K is streamed: half the bytes of ta_decode.
+ *   workspace   as for ta_decode (same size and alignment)
+ *   lse         fp32 [B,Hq] ([B,Sq,Hq])
+ * bf16, d = 128 only (TA_ERR_UNSUPPORTED otherwise).
+ */
+ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
+                    void *workspace, size_t workspace_bytes, float *lse, void *stream);
+
+/*
+ * The paper's two-pass route to the same result as ta_decode: Algorithm 1
+ * (ta_energy: lse) followed by Algorithm 2, the gradient with respect to zeta
+ * taken by hand:  out = Reduce(sum) over chunks of sum_a exp(s_a - lse) v_a.
+ * With lse known no running max and no normaliser are needed and the chunk
+ * partials add up plainly.  K is streamed twice (1.5 x the bytes of ta_decode);
+ * it exists as an on-GPU cross-check of Observation 1 and for callers that
+ * already hold lse.  Arguments as for ta_decode.  bf16, d = 128 only.
+ */
+ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
+                             void *workspace, size_t workspace_bytes,
+                             void *out, float *lse, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

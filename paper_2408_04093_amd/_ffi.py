@@ -62,6 +62,10 @@ def load():
     lib.ta_tree_combine.restype = ctypes.c_int
     lib.ta_decode.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.ta_decode.restype = ctypes.c_int
+    lib.ta_energy.argtypes = [pp, vp, vp, vp, ctypes.c_size_t, vp, vp]
+    lib.ta_energy.restype = ctypes.c_int
+    lib.ta_decode_two_pass.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    lib.ta_decode_two_pass.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -93,6 +97,15 @@ def ta_tree_combine(B, Hq, d, P, part_m, part_l, part_o, out, out_dtype, lse, st
 def ta_decode(problem, q, K, V, workspace, workspace_bytes, out, lse, stream):
     return int(load().ta_decode(ctypes.byref(problem), q, K, V, workspace, int(workspace_bytes),
                                 out, lse, stream or None))
+
+
+def ta_energy(problem, q, K, workspace, workspace_bytes, lse, stream):
+    return int(load().ta_energy(ctypes.byref(problem), q, K, workspace, int(workspace_bytes), lse, stream or None))
+
+
+def ta_decode_two_pass(problem, q, K, V, workspace, workspace_bytes, out, lse, stream):
+    return int(load().ta_decode_two_pass(ctypes.byref(problem), q, K, V, workspace, int(workspace_bytes),
+                                         out, lse, stream or None))
 
 
 # ------------------------------------------------------------------ torch conveniences
@@ -180,4 +193,33 @@ def decode(q, K, V, scale, valid_len=None, out_dtype=None, workspace=None):
                    out.data_ptr(), lse.data_ptr(), _stream())
     if rc:
         raise TAError(rc, "ta_decode")
+    return out, lse
+
+
+def energy(q, K, scale, valid_len=None):
+    """lse [B,Hq] (or [B,Sq,Hq]) = logsumexp of the scaled scores; reads K only."""
+    import torch
+    p = make_problem(q, K, K, scale, valid_len)
+    need = ta_workspace_bytes(p, ta_suggest_chunks(p))
+    workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    lse = torch.empty(tuple(q.shape[:-1]), dtype=torch.float32, device=q.device)
+    rc = ta_energy(p, q.data_ptr(), K.data_ptr(), workspace.data_ptr(), workspace.numel(), lse.data_ptr(), _stream())
+    if rc:
+        raise TAError(rc, "ta_energy")
+    return lse
+
+
+def decode_two_pass(q, K, V, scale, valid_len=None, out_dtype=None):
+    """Energy pass then gradient pass (Algorithms 1 and 2) -> (out, lse), same shapes as decode()."""
+    import torch
+    p = make_problem(q, K, V, scale, valid_len, out_dtype)
+    need = ta_workspace_bytes(p, ta_suggest_chunks(p))
+    workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    out = torch.empty(tuple(q.shape), dtype=torch.bfloat16 if p.out_dtype == TA_BF16 else torch.float32,
+                      device=q.device)
+    lse = torch.empty(tuple(q.shape[:-1]), dtype=torch.float32, device=q.device)
+    rc = ta_decode_two_pass(p, q.data_ptr(), K.data_ptr(), V.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                            out.data_ptr(), lse.data_ptr(), _stream())
+    if rc:
+        raise TAError(rc, "ta_decode_two_pass")
     return out, lse

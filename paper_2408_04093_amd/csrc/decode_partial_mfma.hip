@@ -65,6 +65,16 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
     return u;
 }
 
+// MODE selects what one pass computes (the paper's Algorithm 3 against its
+// Algorithms 1 and 2):
+//   kFull      (m, l, o) per chunk: Algorithm 3 steps 1-2.
+//   kEnergy    (m, l) only, K is the only stream: the energy / logsumexp pass of
+//              Algorithm 1 (zeta = 0 never materialised).
+//   kGradient  o = sum_a exp(s_a - lse) v_a with the final lse given: Algorithm 2
+//              step 5; no running max, no normaliser, partials add up plainly.
+enum { kFull = 0, kEnergy = 1, kGradient = 2 };
+
+template <int MODE>
 __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
     __shared__ float lds_m[kWaves][kMaxHeads];
@@ -94,12 +104,16 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     const int my_tok = t0 + my_row / g;
 
     if (n <= 0) {   // empty chunk: the identity of the merge
-        for (int i = tid; i < nrows * D; i += kThreads)
-            a.part_o[(((int64_t)b * HqV + vhead(i / D)) * a.P + chunk) * D + (i % D)] = 0.f;
-        if (tid < nrows) {
-            const int64_t pi = ((int64_t)b * HqV + vhead(tid)) * a.P + chunk;
-            a.part_m[pi] = -__builtin_huge_valf();
-            a.part_l[pi] = 0.f;
+        if constexpr (MODE != kEnergy) {
+            for (int i = tid; i < nrows * D; i += kThreads)
+                a.part_o[(((int64_t)b * HqV + vhead(i / D)) * a.P + chunk) * D + (i % D)] = 0.f;
+        }
+        if constexpr (MODE != kGradient) {
+            if (tid < nrows) {
+                const int64_t pi = ((int64_t)b * HqV + vhead(tid)) * a.P + chunk;
+                a.part_m[pi] = -__builtin_huge_valf();
+                a.part_l[pi] = 0.f;
+            }
         }
         return;
     }
@@ -181,13 +195,19 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     const float cs = (float)a.c;            // scale * log2(e)
     float m_run = -__builtin_huge_valf();   // running max of head c (log2 units), same in all 4 row groups
     float l_run = 0.f;                      // this lane's share of the normaliser of head c
+    if constexpr (MODE == kGradient) {
+        // the shift is the given total logsumexp (natural log -> log2 units); a row with no key
+        // at all (lse = -inf) gets +inf so that every exp below is exactly 0
+        const float given = a.lse_in[(int64_t)b * HqV + vhead(my_row)];
+        m_run = given == -__builtin_huge_valf() ? __builtin_huge_valf() : given * (float)kLog2e;
+    }
     f32x4 acc[8];                           // acc[j][i] = O[head 4r+i][col 8c+j]
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     v4i kr[8], vr[8];
     issue_k(kr, 0);
-    issue_v(vr, 0);
+    if constexpr (MODE != kEnergy) issue_v(vr, 0);
 
     for (int it = 0; it < n_iters; ++it) {
         const bool masked = it >= n_full;
@@ -217,23 +237,27 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
             sv[e] = s[e >> 2][e & 3] * cs;
             if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim) sv[e] = -__builtin_huge_valf();
         }
-        float mx = sv[0];
+        if constexpr (MODE != kGradient) {
+            float mx = sv[0];
 #pragma unroll
-        for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const bool up = mx > m_run;
-        if (__builtin_amdgcn_ballot_w64(up) != 0) {
-            // raise the running max: rare once the stream is warm
-            const float alpha = up ? exp2_hw(m_run - mx) : 1.0f;
-            m_run = up ? mx : m_run;
-            l_run *= alpha;
-            // acc[.][i] belongs to head 4r+i, whose alpha sits in lane (r, c' = 4r+i)
+            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const bool up = mx > m_run;
+            if (__builtin_amdgcn_ballot_w64(up) != 0) {
+                // raise the running max: rare once the stream is warm
+                const float alpha = up ? exp2_hw(m_run - mx) : 1.0f;
+                m_run = up ? mx : m_run;
+                l_run *= alpha;
+                if constexpr (MODE == kFull) {
+                    // acc[.][i] belongs to head 4r+i, whose alpha sits in lane (r, c' = 4r+i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
+                    for (int i = 0; i < 4; ++i) {
+                        const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j][i] *= ai;
+                        for (int j = 0; j < 8; ++j) acc[j][i] *= ai;
+                    }
+                }
             }
         }
         float p[8];
@@ -243,31 +267,33 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
             if (masked && sv[e] == -__builtin_huge_valf()) p[e] = 0.f;
             l_run += p[e];
         }
-        // P = hi + lo, both bf16, as MFMA A operand: lane (r, head c), k = 8r + e
-        uint32_t ph[4], pl[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
-            const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
-            pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
-        }
-        const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
-        const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
-
-        // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t bj[4];
+        if constexpr (MODE != kEnergy) {
+            // P = hi + lo, both bf16, as MFMA A operand: lane (r, head c), k = 8r + e
+            uint32_t ph[4], pl[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
-                bj[x] = (j & 1) ? ((v0 >> 16) | (v1 & 0xffff0000u)) : ((v0 & 0xffffu) | (v1 << 16));
+                ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
+                const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
+                pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
             }
-            const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbj, acc[j], 0, 0, 0);
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbj, acc[j], 0, 0, 0);
+            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
+            const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
+
+            // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t bj[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
+                    bj[x] = (j & 1) ? ((v0 >> 16) | (v1 & 0xffff0000u)) : ((v0 & 0xffffu) | (v1 << 16));
+                }
+                const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbj, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbj, acc[j], 0, 0, 0);
+            }
+            if (it + 1 < n_iters) issue_v(vr, it + 1);
         }
-        if (it + 1 < n_iters) issue_v(vr, it + 1);
     }
 
     // ---- per-wave totals: the normaliser of head c is spread over the 4 row groups
@@ -277,12 +303,14 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     // ---- merge the waves through LDS (the K staging area is free now)
     __syncthreads();
     float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][nrows][D]
+    if constexpr (MODE != kEnergy) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int h = 4 * r + i;
-        if (h < nrows) {
+        for (int i = 0; i < 4; ++i) {
+            const int h = 4 * r + i;
+            if (h < nrows) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) lds_o[(w * nrows + h) * D + 8 * c + j] = acc[j][i];
+                for (int j = 0; j < 8; ++j) lds_o[(w * nrows + h) * D + 8 * c + j] = acc[j][i];
+            }
         }
     }
     if (r == 0 && c < nrows) {
@@ -291,14 +319,26 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     }
     __syncthreads();
 
-    const int col = tid % D;
-    for (int h = tid / D; h < nrows; h += kThreads / D) {
+    if constexpr (MODE == kGradient) {
+        // weights were already final: the waves' (and later the chunks') numerators simply add
+        const int col = tid % D;
+        for (int h = tid / D; h < nrows; h += kThreads / D) {
+            float ot = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) ot += lds_o[(ww * nrows + h) * D + col];
+            a.part_o[(((int64_t)b * HqV + vhead(h)) * a.P + chunk) * D + col] = ot;
+        }
+        return;
+    }
+
+    const int col = MODE == kEnergy ? 0 : tid % D;
+    for (int h = MODE == kEnergy ? tid : tid / D; h < nrows; h += MODE == kEnergy ? kThreads : kThreads / D) {
         float ms = lds_m[0][h];
 #pragma unroll
         for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
         const int64_t pidx = ((int64_t)b * HqV + vhead(h)) * a.P + chunk;
         if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
-            a.part_o[pidx * D + col] = 0.f;
+            if constexpr (MODE == kFull) a.part_o[pidx * D + col] = 0.f;
             if (col == 0) {
                 a.part_m[pidx] = ms;
                 a.part_l[pidx] = 0.f;
@@ -311,12 +351,12 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
             const float mw = lds_m[ww][h];
             const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
             lt = fmaf(f, lds_l[ww][h], lt);
-            ot = fmaf(f, lds_o[(ww * nrows + h) * D + col], ot);
+            if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * nrows + h) * D + col], ot);
         }
         // natural-log units for the stored max; l and o follow the rounding of the stored value
         const float m_nat = ms * (float)kLn2;
         const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
-        a.part_o[pidx * D + col] = ot * fix;
+        if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
         if (col == 0) {
             a.part_m[pidx] = m_nat;
             a.part_l[pidx] = lt * fix;
@@ -326,17 +366,21 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 
 }  // namespace
 
-hipError_t launch_decode_partial_mfma(const PartialArgs &a, hipStream_t s) {
-    const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
-    hipLaunchKernelGGL(decode_partial_mfma_kernel, dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s) {
+    const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
+    switch (mode) {
+        case kEnergy: hipLaunchKernelGGL(decode_partial_mfma_kernel<kEnergy>, grid, dim3(kThreads), 0, s, a); break;
+        case kGradient: hipLaunchKernelGGL(decode_partial_mfma_kernel<kGradient>, grid, dim3(kThreads), 0, s, a); break;
+        default: hipLaunchKernelGGL(decode_partial_mfma_kernel<kFull>, grid, dim3(kThreads), 0, s, a); break;
+    }
     return hipGetLastError();
 }
 
 int decode_partial_mfma_occupancy() {
     static const int cached = [] {
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel, kThreads, 0) != hipSuccess ||
-            nb < 1) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<kFull>, kThreads, 0) !=
+                hipSuccess || nb < 1) {
             (void)hipGetLastError();
             nb = 2;
         }

@@ -128,6 +128,48 @@ size_t workspace_bytes(const ta_problem *p, int32_t P) {
     return (floats * sizeof(float) + 255) & ~(size_t)255;
 }
 
+// Validate and launch one pass over the chunks.  mode: 0 = (m,l,o); 1 = energy pass (K only; V and
+// part_o unused); 2 = gradient pass given lse_in (part_m, part_l unused).  Modes 1 and 2 exist on
+// the matrix-core kernel only.
+ta_status run_partial(const ta_problem *p, const void *q, const void *K, const void *V, int32_t P,
+                      const int64_t *chunk_bounds, float *part_m, float *part_l, float *part_o,
+                      const float *lse_in, int mode, void *stream) {
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || (mode != 1 && !V)) return TA_ERR_NULL;
+    if (mode != 0 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
+    if (P < 1 || P > (1 << 20)) return TA_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(K) || (V && !aligned16(V))) return TA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(part_m) | reinterpret_cast<uintptr_t>(part_l) |
+         reinterpret_cast<uintptr_t>(part_o) | reinterpret_cast<uintptr_t>(lse_in)) & 3u)
+        return TA_ERR_ALIGN;
+
+    const int eb = elem_bytes(p->qkv_dtype);
+    PartialArgs a{};
+    a.q = q; a.K = K; a.V = V ? V : K;
+    a.valid_len = p->valid_len;
+    a.bounds = chunk_bounds;
+    a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
+    a.lse_in = lse_in;
+    a.N = p->N;
+    a.t = (p->N + P - 1) / P;
+    a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
+    a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
+    a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
+    a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
+    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
+    a.g = p->Hq / p->Hkv;
+    a.Sq = tokens(p);
+    a.tq = tokens_per_workgroup(p);
+    a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
+    a.c = (double)p->scale * kLog2e;
+    if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
+                             ? launch_decode_partial_mfma(a, mode, static_cast<hipStream_t>(stream))
+                             : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -159,38 +201,8 @@ size_t ta_workspace_bytes(const ta_problem *p, int32_t P) {
 ta_status ta_decode_partial(const ta_problem *p, const void *q, const void *K, const void *V,
                             int32_t P, const int64_t *chunk_bounds,
                             float *part_m, float *part_l, float *part_o, void *stream) {
-    const ta_status st = check_problem(p);
-    if (st != TA_OK) return st;
-    if (!q || !K || !V || !part_m || !part_l || !part_o) return TA_ERR_NULL;
-    if (P < 1 || P > (1 << 20)) return TA_ERR_SHAPE;
-    if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TA_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(part_m) | reinterpret_cast<uintptr_t>(part_l) |
-         reinterpret_cast<uintptr_t>(part_o)) & 3u)
-        return TA_ERR_ALIGN;
-
-    const int eb = elem_bytes(p->qkv_dtype);
-    PartialArgs a{};
-    a.q = q; a.K = K; a.V = V;
-    a.valid_len = p->valid_len;
-    a.bounds = chunk_bounds;
-    a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
-    a.N = p->N;
-    a.t = (p->N + P - 1) / P;
-    a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
-    a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
-    a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
-    a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
-    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
-    a.g = p->Hq / p->Hkv;
-    a.Sq = tokens(p);
-    a.tq = tokens_per_workgroup(p);
-    a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
-    a.c = (double)p->scale * kLog2e;
-    if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
-    const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
-                             ? launch_decode_partial_mfma(a, static_cast<hipStream_t>(stream))
-                             : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+    if (!part_m || !part_l || !part_o) return TA_ERR_NULL;
+    return run_partial(p, q, K, V, P, chunk_bounds, part_m, part_l, part_o, nullptr, 0, stream);
 }
 
 ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
@@ -231,6 +243,45 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     if (s2 != TA_OK) return s2;
     return ta_tree_combine(p->B, tokens(p) * p->Hq, p->d, P, part_m, part_l, part_o, out, p->out_dtype, lse,
                            stream);
+}
+
+ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
+                    void *workspace, size_t workspace_bytes_given, float *lse, void *stream) {
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || !workspace || !lse) return TA_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TA_ERR_ALIGN;
+    const int32_t P = suggest_chunks(p, device_compute_units());
+    if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
+    const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;
+    float *part_m = static_cast<float *>(workspace) + bhp * p->d;      // same slots as in ta_decode
+    float *part_l = part_m + bhp;
+    const ta_status s2 = run_partial(p, q, K, nullptr, P, nullptr, part_m, part_l, nullptr, nullptr, 1, stream);
+    if (s2 != TA_OK) return s2;
+    CombineArgs c{};
+    c.part_m = part_m; c.part_l = part_l;
+    c.lse = lse;
+    c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = P;
+    return launch_energy_combine(c, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
+ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
+                             void *workspace, size_t workspace_bytes_given,
+                             void *out, float *lse, void *stream) {
+    if (!V || !out) return TA_ERR_NULL;
+    const ta_status s1 = ta_energy(p, q, K, workspace, workspace_bytes_given, lse, stream);
+    if (s1 != TA_OK) return s1;
+    if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
+    const int32_t P = suggest_chunks(p, device_compute_units());
+    float *part_o = static_cast<float *>(workspace);
+    const ta_status s2 = run_partial(p, q, K, V, P, nullptr, nullptr, nullptr, part_o, lse, 2, stream);
+    if (s2 != TA_OK) return s2;
+    CombineArgs c{};
+    c.part_o = part_o;
+    c.out = out;
+    c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = P;
+    c.out_dtype = p->out_dtype;
+    return launch_sum_partials(c, p->d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
 }  // extern "C"

@@ -16,6 +16,7 @@ struct PartialArgs {
     const int32_t *valid_len;   // device [B] or null
     const int64_t *bounds;      // device [P+1] or null
     float *part_m, *part_l, *part_o;
+    const float *lse_in;        // gradient pass only: total logsumexp per (b, token, head)
     int64_t N;
     int64_t t;                  // keys per chunk when bounds == null
     int64_t k_sb, k_sh, v_sb, v_sh;   // elements
@@ -35,6 +36,9 @@ struct CombineArgs {
     int32_t B, Hq, P;
     int32_t out_dtype;
 };
+// energy pass: lse from (m, l) partials only; gradient pass: out = plain sum of the partial numerators
+hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s);
+hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s);
 
 // bf16 with d = 128 runs on the matrix-core kernel (any group size up to 16 in
 // one pass); everything else on the VALU kernel.
@@ -50,7 +54,8 @@ inline int heads_per_workgroup(int dtype, int d, int g) {
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
 // resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
 int decode_partial_occupancy(int dtype, int d, int gt);
-hipError_t launch_decode_partial_mfma(const PartialArgs &a, hipStream_t s);   // bf16, d = 128, slices = 1
+// bf16, d = 128.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s);
 int decode_partial_mfma_occupancy();
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 

@@ -129,12 +129,84 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
     if (tid == 0 && blockIdx.x % kSlices == 0) a.lse[bh] = mstar + logf(lstar);
 }
 
+// Energy pass: lse = m* + log(sum_j exp(m_j - m*) l_j) from the (m, l) partials alone
+// (Algorithm 1 steps 4-6 as one reduction).  One wavefront per (b, h).
+__global__ void __launch_bounds__(kWave) energy_combine_kernel(const CombineArgs a) {
+    constexpr float kLog2eF = 1.4426950408889634074f;
+    const int lane = threadIdx.x;
+    const int64_t bh = blockIdx.x;
+    const float *pm = a.part_m + bh * a.P;
+    const float *pl = a.part_l + bh * a.P;
+    float mx = -__builtin_huge_valf();
+    for (int j = lane; j < a.P; j += kWave)
+        if (pl[j] > 0.f) mx = fmaxf(mx, pm[j]);
+    mx = wave_max(mx);
+    if (mx == -__builtin_huge_valf()) {
+        if (lane == 0) a.lse[bh] = mx;
+        return;
+    }
+    float ls = 0.f;
+    for (int j = lane; j < a.P; j += kWave) {
+        const float lj = pl[j];
+        if (lj > 0.f) ls = fmaf(exp2_hw((pm[j] - mx) * kLog2eF), lj, ls);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off);
+    if (lane == 0) a.lse[bh] = mx + logf(ls);
+}
+
+// Gradient pass (Algorithm 2 step 6): out = Reduce(sum) of the per-chunk numerators, no weights.
+template <int D>
+__global__ void __launch_bounds__(kThreads) sum_partials_kernel(const CombineArgs a) {
+    constexpr int kSlices = D / kSlice;
+    const int tid = threadIdx.x;
+    const int c = tid & (kSlice - 1);
+    const int r = tid / kSlice;
+    const int64_t bh = blockIdx.x / kSlices;
+    const int col = (blockIdx.x % kSlices) * kSlice + c;
+    const float *po = a.part_o + bh * a.P * D + col;
+    __shared__ float sh_o[kGroups][kSlice];
+
+    float acc = 0.f;
+    for (int j0 = r; j0 < a.P; j0 += kGroups * kBatch) {
+        float x[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int j = j0 + i * kGroups;
+            x[i] = j < a.P ? po[(int64_t)j * D] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) acc += x[i];
+    }
+    sh_o[r][c] = acc;
+    __syncthreads();
+    if (tid < kSlice) {
+        float o = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < kGroups; ++rr) o += sh_o[rr][tid];
+        if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[bh * D + col] = f32_to_bf16_rne(o);
+        else reinterpret_cast<float *>(a.out)[bh * D + col] = o;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
     const dim3 grid((uint32_t)((int64_t)a.B * a.Hq * (d / kSlice)));
     if (d == 128) hipLaunchKernelGGL((tree_combine_kernel<128>), grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL((tree_combine_kernel<64>), grid, dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(energy_combine_kernel, dim3((uint32_t)((int64_t)a.B * a.Hq)), dim3(kWave), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s) {
+    const dim3 grid((uint32_t)((int64_t)a.B * a.Hq * (d / kSlice)));
+    if (d == 128) hipLaunchKernelGGL((sum_partials_kernel<128>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((sum_partials_kernel<64>), grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -44,7 +44,7 @@ def llama_problem():
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted([
         "ta_status_string", "ta_suggest_chunks", "ta_workspace_bytes",
-        "ta_decode_partial", "ta_tree_combine", "ta_decode"])
+        "ta_decode_partial", "ta_tree_combine", "ta_decode", "ta_energy", "ta_decode_two_pass"])
 
 
 def test_library_exports_every_declared_symbol(lib):

@@ -517,3 +517,58 @@ def test_graph_capture_and_replay():
         eager = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
         torch.cuda.synchronize()
         assert torch.equal(eager[0], out) and torch.equal(eager[1], lse)
+
+
+# ------------------------------------------------------------------ energy pass and the two-pass route (Algorithms 1 and 2)
+@pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [(1, 1, 4, 1, 1), (2, 1, 8, 2, 1000), (1, 1, 16, 1, 4099),
+                                            (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000)])
+def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N):
+    if Sq == 1:
+        w = W.make_qkv(B, Hq, Hkv, 128, N, torch.bfloat16, seed=300 + N, device="cuda")
+        ref_fn = oracle.decode
+    else:
+        w = W.make_multi(B, Sq, Hq, Hkv, 128, N, torch.bfloat16, seed=300 + N, device="cuda")
+        ref_fn = oracle.decode_causal
+    if B > 1:
+        w.valid_len = torch.tensor([N, N // 2][:B], dtype=torch.int32, device="cuda")
+    vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
+    ref_out, ref_lse = ref_fn(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
+    # Algorithm 1 alone: lse = F(0), K is the only stream
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    # Algorithms 1 + 2
+    out2, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    out2b, _ = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_BF16)
+    # Algorithm 3 (the one-pass path) for comparison
+    out3, lse3 = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert lse_err(lse_e.cpu().numpy(), ref_lse) <= TOL_LSE
+    assert torch.equal(lse_e, lse2)
+    assert row_rel_l2(out2.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    check_bf16_output(out2b.float().cpu().numpy(), out2.cpu().numpy(), ref_out)
+    # Observation 1 on the GPU: the gradient route and the one-pass route agree
+    assert row_rel_l2(out2.cpu().numpy(), out3.cpu().numpy().astype(np.float64)) <= 2e-5
+    assert lse_err(lse2.cpu().numpy(), lse3.cpu().numpy().astype(np.float64)) <= 1e-5
+
+
+def test_energy_of_an_empty_sequence_and_unsupported_types():
+    w = W.make_qkv(2, 4, 1, 128, 64, torch.bfloat16, seed=2, device="cuda")
+    w.valid_len = torch.tensor([0, 64], dtype=torch.int32, device="cuda")
+    lse = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    out, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert torch.isneginf(lse[0]).all() and torch.isfinite(lse[1]).all()
+    assert not out[0].any().item() and torch.isfinite(out).all()
+    w32 = W.make_qkv(1, 2, 1, 64, 64, torch.float32, seed=2, device="cuda")
+    with pytest.raises(ta.TAError) as e:
+        ta.energy(w32.q, w32.K, w32.scale)
+    assert e.value.code == 6
+
+
+def test_energy_llama_128k_full():
+    w = W.llama128k(device="cuda")
+    ref_out, ref_lse = oracle_of(w)
+    lse = ta.energy(w.q, w.K, w.scale)
+    out, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
