@@ -38,10 +38,10 @@ def build_workload(name, device, copy):
         return W.ragged(device=device)
     if name == "combine":
         return W.combine_stress(device=device)
-    if name == "llama128k_sq4":
-        # 4 query tokens (speculative decoding) on the llama128k shape: 4 tokens x 4 heads = 16 MFMA rows
-        return W.make_multi(1, 4, 32, 8, 128, 131072, torch.bfloat16, W.BASE_SEED + 6 + 1000 * copy, device,
-                            name="llama128k_sq4")
+    if name.startswith("llama128k_sq"):
+        # several query tokens (speculative decoding) on the llama128k shape: Sq tokens x 4 heads MFMA rows
+        return W.make_multi(1, int(name[12:]), 32, 8, 128, 131072, torch.bfloat16,
+                            W.BASE_SEED + 6 + 1000 * copy, device, name=name)
     if name in ("shard80k", "shard40k"):
         w = W.paper_shard(N=80000 if name == "shard80k" else 40000, device=device)
         if copy:   # distinct values per rotating copy
@@ -242,7 +242,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
                     help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "

@@ -43,8 +43,8 @@
  *     lse = -inf.  Shapes gain a token axis: q and out [B,Sq,Hq,d],
  *     lse [B,Sq,Hq], partials [B,Sq,Hq,P] and [B,Sq,Hq,P,d]; for
  *     ta_tree_combine pass Sq*Hq as Hq.  All tokens and heads of a KV group
- *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 16; beyond that the
- *     tokens are processed in slices of floor(16 / (Hq/Hkv)), each slice
+ *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 64; beyond that the
+ *     tokens are processed in slices of floor(64 / (Hq/Hkv)), each slice
  *     reading K/V once.  Sq > 1 needs bf16 inputs and d = 128.
  */
 #ifndef TREE_ATTN_H

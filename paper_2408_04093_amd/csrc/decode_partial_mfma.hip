@@ -46,6 +46,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef TA_AUX
 #define TA_AUX 2   // non-temporal K/V loads
 #endif
+#ifndef TA_DEPTH
+#define TA_DEPTH 1 // register tiles (steps of K and V) kept in flight per wave
+#endif
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
@@ -72,9 +75,11 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
 //              Algorithm 1 (zeta = 0 never materialised).
 //   kGradient  o = sum_a exp(s_a - lse) v_a with the final lse given: Algorithm 2
 //              step 5; no running max, no normaliser, partials add up plainly.
+// NRB is the number of 16-row blocks of (query token, head) pairs that share the
+// K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
 enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 
-template <int MODE>
+template <int MODE, int NRB>
 __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
     __shared__ float lds_m[kWaves][kMaxHeads];
@@ -83,7 +88,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = lane >> 4, c = lane & 15;     // row group / (column block or head)
+    const int r = lane >> 4, c = lane & 15;     // row group / (column block or row within a row block)
     const int g = a.g;                          // heads of the group, all in this workgroup
 
     __shared__ int sh_rank[kMaxRankedChunks + 1];
@@ -96,12 +101,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     // query tokens [t0, t0 + ntok) of the Sq (one token in plain decode)
     const int t0 = cr.slice * a.tq;
     const int ntok = (a.Sq - t0) < a.tq ? (a.Sq - t0) : a.tq;
-    const int nrows = ntok * g;
+    const int nrows = ntok * g;                 // <= 16 * NRB
     const int HqV = a.Sq * a.Hq;                // (token, head) pairs per sequence
-    // virtual head of row x: token-major [Sq][Hq]
+    // virtual head of a row: token-major [Sq][Hq]
     auto vhead = [&](int row) { return (t0 + row / g) * a.Hq + hk * g + row % g; };
-    const int my_row = c < nrows ? c : 0;       // row served by this lane as "head" lane
-    const int my_tok = t0 + my_row / g;
 
     if (n <= 0) {   // empty chunk: the identity of the merge
         if constexpr (MODE != kEnergy) {
@@ -118,26 +121,29 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
         return;
     }
 
-    // Causal limit among the query tokens: token t sees keys < L - Sq + 1 + t.
-    // nlim: chunk-relative count of keys this lane's row may use; n_common: keys every row may use.
-    int nlim, n_common;
-    {
-        int64_t lim = cr.L - a.Sq + 1 + my_tok - lo;
-        nlim = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
-        int64_t limc = cr.L - a.Sq + 1 + t0 - lo;
-        n_common = (int)(limc < 0 ? 0 : (limc > n ? n : limc));
-    }
-
-    // Q^T as MFMA B operand: lane (kb = r, row = c) holds q[row][32t + 8r .. +8], zero for padded rows
-    bf16x8 qb[4];
-    {
-        const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row)) * D + 8 * r) * 2;
+    // Per row block: the row this lane serves as "row lane" (row = 16 rb + c), its causal limit
+    // (token t sees keys < L - Sq + 1 + t; chunk-relative, clamped to [0, n]) and its slice of
+    // Q^T as MFMA B operand: lane (kb = r, row c) holds q[row][32t + 8r .. +8], zero for padding.
+    int my_row[NRB], nlim[NRB];
+    bf16x8 qb[NRB][4];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int row = 16 * rb + c;
+        my_row[rb] = row < nrows ? row : 0;
+        const int64_t lim = cr.L - a.Sq + 1 + (t0 + my_row[rb] / g) - lo;
+        nlim[rb] = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
+        const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row[rb])) * D + 8 * r) * 2;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
-            if (c >= nrows) raw = v4i{0, 0, 0, 0};
-            qb[t] = __builtin_bit_cast(bf16x8, raw);
+            if (row >= nrows) raw = v4i{0, 0, 0, 0};
+            qb[rb][t] = __builtin_bit_cast(bf16x8, raw);
         }
+    }
+    int n_common;   // keys every row may use: steps below it need no masking
+    {
+        const int64_t limc = cr.L - a.Sq + 1 + t0 - lo;
+        n_common = (int)(limc < 0 ? 0 : (limc > n ? n : limc));
     }
 
     const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * 2 + lo * (int64_t)a.k_row_bytes;
@@ -167,7 +173,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 kr[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[e] + inc), 0, TA_AUX);
-        } else {   // ragged last step: rows past the chunk are redirected to its last row
+        } else {   // ragged last steps: rows past the chunk are redirected to its last row
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 int row = it * ROWS_ITER + w * kTile + trow[e];
@@ -192,94 +198,108 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
         }
     };
 
-    const float cs = (float)a.c;            // scale * log2(e)
-    float m_run = -__builtin_huge_valf();   // running max of head c (log2 units), same in all 4 row groups
-    float l_run = 0.f;                      // this lane's share of the normaliser of head c
-    if constexpr (MODE == kGradient) {
-        // the shift is the given total logsumexp (natural log -> log2 units); a row with no key
-        // at all (lse = -inf) gets +inf so that every exp below is exactly 0
-        const float given = a.lse_in[(int64_t)b * HqV + vhead(my_row)];
-        m_run = given == -__builtin_huge_valf() ? __builtin_huge_valf() : given * (float)kLog2e;
-    }
-    f32x4 acc[8];                           // acc[j][i] = O[head 4r+i][col 8c+j]
+    const float cs = (float)a.c;   // scale * log2(e)
+    float m_run[NRB];              // running max of this lane's row (log2 units), same in all 4 row groups
+    float l_run[NRB];              // this lane's share of the row's normaliser
+    f32x4 acc[NRB][8];             // acc[rb][j][i] = O[row 16rb + 4r + i][col 8c + j]
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < NRB; ++rb) {
+        m_run[rb] = -__builtin_huge_valf();
+        l_run[rb] = 0.f;
+        if constexpr (MODE == kGradient) {
+            // the shift is the given total logsumexp (natural log -> log2 units); a row with no key
+            // at all (lse = -inf) gets +inf so that every exp below is exactly 0
+            const float given = a.lse_in[(int64_t)b * HqV + vhead(my_row[rb])];
+            m_run[rb] = given == -__builtin_huge_valf() ? __builtin_huge_valf() : given * (float)kLog2e;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
-    v4i kr[8], vr[8];
-    issue_k(kr, 0);
-    if constexpr (MODE != kEnergy) issue_v(vr, 0);
-
-    for (int it = 0; it < n_iters; ++it) {
+    // One pipeline step on the register tiles (kr, vr) holding step `it`; the tiles are refilled
+    // with step it + TA_DEPTH as soon as they have been consumed.
+    auto step = [&](v4i (&kr)[8], v4i (&vr)[8], int it) {
         const bool masked = it >= n_full;
         // ---- K tile: registers -> LDS (row-major, padded) -> A layout
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             *reinterpret_cast<v4i *>(stage + trow[e] * kPitch + c * 16) = kr[e];
-        if (it + 1 < n_iters) issue_k(kr, it + 1);    // next K tile in flight during this step
+        if (it + TA_DEPTH < n_iters) issue_k(kr, it + TA_DEPTH);
 
-        f32x4 s[2];
+        f32x4 s[NRB][2];
 #pragma unroll
         for (int G = 0; G < 2; ++G) {
             v4i af[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 af[t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
-            s[G] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                s[G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), qb[t], s[G], 0, 0, 0);
+            for (int rb = 0; rb < NRB; ++rb) {
+                s[rb][G] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), qb[rb][t],
+                                                                        s[rb][G], 0, 0, 0);
+            }
         }
 
-        // ---- online softmax for head c over this lane's 8 keys (slot e = 4G + i)
-        float sv[8];
+        // ---- online softmax: per row block this lane owns 8 keys (slot e = 4G + i) of one row
+        bf16x8 pa_hi[NRB], pa_lo[NRB];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            sv[e] = s[e >> 2][e & 3] * cs;
-            if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim) sv[e] = -__builtin_huge_valf();
-        }
-        if constexpr (MODE != kGradient) {
-            float mx = sv[0];
+        for (int rb = 0; rb < NRB; ++rb) {
+            float sv[8];
 #pragma unroll
-            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const bool up = mx > m_run;
-            if (__builtin_amdgcn_ballot_w64(up) != 0) {
-                // raise the running max: rare once the stream is warm
-                const float alpha = up ? exp2_hw(m_run - mx) : 1.0f;
-                m_run = up ? mx : m_run;
-                l_run *= alpha;
-                if constexpr (MODE == kFull) {
-                    // acc[.][i] belongs to head 4r+i, whose alpha sits in lane (r, c' = 4r+i)
+            for (int e = 0; e < 8; ++e) {
+                sv[e] = s[rb][e >> 2][e & 3] * cs;
+                if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[e] = -__builtin_huge_valf();
+            }
+            if constexpr (MODE != kGradient) {
+                float mx = sv[0];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
+                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const bool up = mx > m_run[rb];
+                if (__builtin_amdgcn_ballot_w64(up) != 0) {
+                    // raise the running max: rare once the stream is warm
+                    const float alpha = up ? exp2_hw(m_run[rb] - mx) : 1.0f;
+                    m_run[rb] = up ? mx : m_run[rb];
+                    l_run[rb] *= alpha;
+                    if constexpr (MODE == kFull) {
+                        // acc[rb][.][i] belongs to row 4r+i of the block, whose alpha sits in lane (r, 4r+i)
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[j][i] *= ai;
+                        for (int i = 0; i < 4; ++i) {
+                            const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) acc[rb][j][i] *= ai;
+                        }
                     }
                 }
             }
-        }
-        float p[8];
+            float p[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            p[e] = exp2_hw(sv[e] - m_run);
-            if (masked && sv[e] == -__builtin_huge_valf()) p[e] = 0.f;
-            l_run += p[e];
-        }
-        if constexpr (MODE != kEnergy) {
-            // P = hi + lo, both bf16, as MFMA A operand: lane (r, head c), k = 8r + e
-            uint32_t ph[4], pl[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
-                const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
-                pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
+            for (int e = 0; e < 8; ++e) {
+                p[e] = exp2_hw(sv[e] - m_run[rb]);
+                if (masked && sv[e] == -__builtin_huge_valf()) p[e] = 0.f;
+                l_run[rb] += p[e];
             }
-            const bf16x8 pa_hi = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
-            const bf16x8 pa_lo = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
+            if constexpr (MODE != kEnergy) {
+                // P = hi + lo, both bf16, as MFMA A operand: lane (r, row c), k = 8r + e
+                uint32_t ph[4], pl[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
+                    const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
+                    pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
+                }
+                pa_hi[rb] = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
+                pa_lo[rb] = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
+            }
+        }
 
-            // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout
+        if constexpr (MODE != kEnergy) {
+            // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout (once
+            // for all row blocks)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 uint32_t bj[4];
@@ -289,97 +309,128 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                     bj[x] = (j & 1) ? ((v0 >> 16) | (v1 & 0xffff0000u)) : ((v0 & 0xffffu) | (v1 << 16));
                 }
                 const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vbj, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vbj, acc[j], 0, 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) {
+                    acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi[rb], vbj, acc[rb][j], 0, 0, 0);
+                    acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo[rb], vbj, acc[rb][j], 0, 0, 0);
+                }
             }
-            if (it + 1 < n_iters) issue_v(vr, it + 1);
+            if (it + TA_DEPTH < n_iters) issue_v(vr, it + TA_DEPTH);
+        }
+    };
+
+    // TA_DEPTH register tiles in rotation (1 measured as good as 2 or 3: the stream is DRAM-bound,
+    // not latency-bound, and one tile keeps two workgroups resident per CU)
+    v4i kr[TA_DEPTH][8], vr[TA_DEPTH][8];
+#pragma unroll
+    for (int x = 0; x < TA_DEPTH; ++x) {
+        if (x < n_iters) {
+            issue_k(kr[x], x);
+            if constexpr (MODE != kEnergy) issue_v(vr[x], x);
         }
     }
-
-    // ---- per-wave totals: the normaliser of head c is spread over the 4 row groups
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-
-    // ---- merge the waves through LDS (the K staging area is free now)
-    __syncthreads();
-    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][nrows][D]
-    if constexpr (MODE != kEnergy) {
+    for (int it = 0; it < n_iters; it += TA_DEPTH) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int h = 4 * r + i;
-            if (h < nrows) {
+        for (int x = 0; x < TA_DEPTH; ++x)
+            if (it + x < n_iters) step(kr[x], vr[x], it + x);
+    }
+
+    // ---- merge the waves through LDS, one row block at a time (the K staging area is free now)
+    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][16][D]
 #pragma unroll
-                for (int j = 0; j < 8; ++j) lds_o[(w * nrows + h) * D + 8 * c + j] = acc[j][i];
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int brows = nrows - 16 * rb < 16 ? nrows - 16 * rb : 16;   // rows of this block
+        if (brows <= 0) break;
+        // the row's normaliser is spread over the 4 row groups of the wave
+        float lw = l_run[rb];
+        lw += __shfl_xor(lw, 16);
+        lw += __shfl_xor(lw, 32);
+        __syncthreads();
+        if constexpr (MODE != kEnergy) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int h = 4 * r + i;
+                if (h < brows) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) lds_o[(w * 16 + h) * D + 8 * c + j] = acc[rb][j][i];
+                }
             }
         }
-    }
-    if (r == 0 && c < nrows) {
-        lds_m[w][c] = m_run;
-        lds_l[w][c] = l_run;
-    }
-    __syncthreads();
-
-    if constexpr (MODE == kGradient) {
-        // weights were already final: the waves' (and later the chunks') numerators simply add
-        const int col = tid % D;
-        for (int h = tid / D; h < nrows; h += kThreads / D) {
-            float ot = 0.f;
-#pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) ot += lds_o[(ww * nrows + h) * D + col];
-            a.part_o[(((int64_t)b * HqV + vhead(h)) * a.P + chunk) * D + col] = ot;
+        if (r == 0 && c < brows) {
+            lds_m[w][c] = m_run[rb];
+            lds_l[w][c] = lw;
         }
-        return;
-    }
+        __syncthreads();
 
-    const int col = MODE == kEnergy ? 0 : tid % D;
-    for (int h = MODE == kEnergy ? tid : tid / D; h < nrows; h += MODE == kEnergy ? kThreads : kThreads / D) {
-        float ms = lds_m[0][h];
+        if constexpr (MODE == kGradient) {
+            // weights were already final: the waves' (and later the chunks') numerators simply add
+            const int col = tid % D;
+            for (int h = tid / D; h < brows; h += kThreads / D) {
+                float ot = 0.f;
 #pragma unroll
-        for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
-        const int64_t pidx = ((int64_t)b * HqV + vhead(h)) * a.P + chunk;
-        if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
-            if constexpr (MODE == kFull) a.part_o[pidx * D + col] = 0.f;
-            if (col == 0) {
-                a.part_m[pidx] = ms;
-                a.part_l[pidx] = 0.f;
+                for (int ww = 0; ww < kWaves; ++ww) ot += lds_o[(ww * 16 + h) * D + col];
+                a.part_o[(((int64_t)b * HqV + vhead(16 * rb + h)) * a.P + chunk) * D + col] = ot;
             }
-            continue;
-        }
-        float lt = 0.f, ot = 0.f;
+        } else {
+            const int col = MODE == kEnergy ? 0 : tid % D;
+            for (int h = MODE == kEnergy ? tid : tid / D; h < brows; h += MODE == kEnergy ? kThreads : kThreads / D) {
+                float ms = lds_m[0][h];
 #pragma unroll
-        for (int ww = 0; ww < kWaves; ++ww) {
-            const float mw = lds_m[ww][h];
-            const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
-            lt = fmaf(f, lds_l[ww][h], lt);
-            if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * nrows + h) * D + col], ot);
-        }
-        // natural-log units for the stored max; l and o follow the rounding of the stored value
-        const float m_nat = ms * (float)kLn2;
-        const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
-        if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
-        if (col == 0) {
-            a.part_m[pidx] = m_nat;
-            a.part_l[pidx] = lt * fix;
+                for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
+                const int64_t pidx = ((int64_t)b * HqV + vhead(16 * rb + h)) * a.P + chunk;
+                if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
+                    if constexpr (MODE == kFull) a.part_o[pidx * D + col] = 0.f;
+                    if (col == 0) {
+                        a.part_m[pidx] = ms;
+                        a.part_l[pidx] = 0.f;
+                    }
+                    continue;
+                }
+                float lt = 0.f, ot = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) {
+                    const float mw = lds_m[ww][h];
+                    const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
+                    lt = fmaf(f, lds_l[ww][h], lt);
+                    if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * 16 + h) * D + col], ot);
+                }
+                // natural-log units for the stored max; l and o follow the rounding of the stored value
+                const float m_nat = ms * (float)kLn2;
+                const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
+                if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
+                if (col == 0) {
+                    a.part_m[pidx] = m_nat;
+                    a.part_l[pidx] = lt * fix;
+                }
+            }
         }
     }
 }
 
 }  // namespace
 
-hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s) {
-    const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
+template <int NRB>
+hipError_t launch_mode(const PartialArgs &a, int mode, dim3 grid, hipStream_t s) {
     switch (mode) {
-        case kEnergy: hipLaunchKernelGGL(decode_partial_mfma_kernel<kEnergy>, grid, dim3(kThreads), 0, s, a); break;
-        case kGradient: hipLaunchKernelGGL(decode_partial_mfma_kernel<kGradient>, grid, dim3(kThreads), 0, s, a); break;
-        default: hipLaunchKernelGGL(decode_partial_mfma_kernel<kFull>, grid, dim3(kThreads), 0, s, a); break;
+        case kEnergy: hipLaunchKernelGGL((decode_partial_mfma_kernel<kEnergy, NRB>), grid, dim3(kThreads), 0, s, a); break;
+        case kGradient: hipLaunchKernelGGL((decode_partial_mfma_kernel<kGradient, NRB>), grid, dim3(kThreads), 0, s, a); break;
+        default: hipLaunchKernelGGL((decode_partial_mfma_kernel<kFull, NRB>), grid, dim3(kThreads), 0, s, a); break;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s) {
+    const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
+    const int rows = a.tq * a.g;
+    if (rows <= 16) return launch_mode<1>(a, mode, grid, s);
+    if (rows <= 32) return launch_mode<2>(a, mode, grid, s);
+    return launch_mode<4>(a, mode, grid, s);
 }
 
 int decode_partial_mfma_occupancy() {
     static const int cached = [] {
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<kFull>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<kFull, 1>, kThreads, 0) !=
                 hipSuccess || nb < 1) {
             (void)hipGetLastError();
             nb = 2;

@@ -13,9 +13,10 @@ using namespace ta;
 
 inline int elem_bytes(int dt) { return dt == TA_BF16 ? 2 : 4; }
 inline int tokens(const ta_problem *p) { return p->Sq > 1 ? p->Sq : 1; }
-// query tokens per workgroup on the matrix-core kernel: tokens * group heads fill the 16 MFMA rows
+// query tokens per workgroup on the matrix-core kernel: (token, head) pairs fill up to 4 blocks of
+// 16 MFMA rows that share one pass over K/V
 inline int tokens_per_workgroup(const ta_problem *p) {
-    const int tq = 16 / (p->Hq / p->Hkv);
+    const int tq = 64 / (p->Hq / p->Hkv);
     return tq < tokens(p) ? tq : tokens(p);
 }
 // independent workgroup groups per chunk index

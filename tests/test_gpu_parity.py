@@ -438,7 +438,9 @@ def check_multi(w):
 
 @pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [
     (1, 2, 4, 1, 300), (2, 4, 8, 2, 1000), (1, 16, 1, 1, 777), (1, 3, 8, 1, 513),
-    (1, 8, 32, 8, 4099), (2, 5, 16, 16, 129), (1, 7, 12, 2, 2048), (1, 4, 16, 1, 640)])
+    (1, 8, 32, 8, 4099), (2, 5, 16, 16, 129), (1, 7, 12, 2, 2048), (1, 4, 16, 1, 640),
+    # 17..64 (token, head) rows: two and four row blocks in one pass; beyond 64: token slices
+    (1, 16, 32, 8, 1500), (1, 5, 8, 1, 900), (2, 20, 4, 1, 700), (1, 5, 16, 1, 333), (1, 40, 2, 2, 400)])
 def test_multi_token_causal_decode(B, Sq, Hq, Hkv, N):
     w = W.make_multi(B, Sq, Hq, Hkv, 128, N, torch.bfloat16, seed=77 + Sq + N, device="cuda")
     check_multi(w)
@@ -472,9 +474,10 @@ def test_multi_token_needs_bf16_d128():
     assert e.value.code == 6
 
 
-def test_multi_token_llama_shape_full():
-    """Llama head shape, 4 draft tokens (16 MFMA rows) over 128k keys: one pass over K/V."""
-    w = W.make_multi(1, 4, 32, 8, 128, 131072, torch.bfloat16, seed=W.BASE_SEED + 6, device="cuda")
+@pytest.mark.parametrize("Sq", [4, 16])
+def test_multi_token_llama_shape_full(Sq):
+    """Llama head shape, 4 / 16 draft tokens (16 / 64 MFMA rows) over 128k keys: one pass over K/V."""
+    w = W.make_multi(1, Sq, 32, 8, 128, 131072, torch.bfloat16, seed=W.BASE_SEED + 6, device="cuda")
     check_multi(w)
 
 
@@ -521,7 +524,8 @@ def test_graph_capture_and_replay():
 
 # ------------------------------------------------------------------ energy pass and the two-pass route (Algorithms 1 and 2)
 @pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [(1, 1, 4, 1, 1), (2, 1, 8, 2, 1000), (1, 1, 16, 1, 4099),
-                                            (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000)])
+                                            (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000), (1, 12, 8, 2, 600),
+                                            (1, 9, 16, 2, 450)])
 def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N):
     if Sq == 1:
         w = W.make_qkv(B, Hq, Hkv, 128, N, torch.bfloat16, seed=300 + N, device="cuda")
