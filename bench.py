@@ -27,10 +27,15 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 LLC_BYTES = 256 << 20      # Infinity Cache
 
 
+KEYS_OVERRIDE = None    # --keys: context length for the llama128k workload (characterisation sweeps)
+
+
 def build_workload(name, device, copy):
     import torch
     import ta_workloads as W
     if name == "llama128k":
+        if KEYS_OVERRIDE:
+            return W.llama128k(N=KEYS_OVERRIDE, device=device, seed_offset=copy)
         return W.llama128k(device=device, seed_offset=copy)
     if name == "million":
         return W.million(device=device)
@@ -81,7 +86,7 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"
     # distinct input copies so that consecutive steps never hit the last-level cache
     w0 = build_workload(name, dev, 0)
     kv = w0.K.numel() * w0.K.element_size() * 2
-    n_copies = 1 if kv >= 8 * LLC_BYTES else max(2, -(-8 * LLC_BYTES // kv))
+    n_copies = 1 if kv >= 8 * LLC_BYTES else min(64, max(2, -(-8 * LLC_BYTES // kv)))
     ws = [w0] + [build_workload(name, dev, c) for c in range(1, n_copies)]
     B, Hq, Hkv, d, N = w0.shape
     alg = algorithmic_bytes(w0)
@@ -247,6 +252,8 @@ def main():
     ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
                     help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "
                          "two_pass = ta_decode_two_pass (Algorithms 1 + 2)")
+    ap.add_argument("--keys", type=int, default=0,
+                    help="override the context length N of the llama128k workload (sweeps; not the headline)")
     ap.add_argument("--graph", action="store_true",
                     help="launch the timed steps by replaying a captured HIP graph instead of eagerly")
     ap.add_argument("--no-extra", action="store_true",
@@ -254,6 +261,9 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1")
+    if args.keys:
+        global KEYS_OVERRIDE
+        KEYS_OVERRIDE = args.keys
 
     import torch
     import paper_2408_04093_amd as ta
@@ -267,7 +277,7 @@ def main():
 
     result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline and args.op == "decode",
                           args.graph, args.op)
-    if args.workload == "llama128k" and not args.no_extra and args.op == "decode":
+    if args.workload == "llama128k" and not args.no_extra and args.op == "decode" and not args.keys:
         # the metric is quoted at 128k and at 1M keys: report the second size in the same line
         torch.cuda.empty_cache()
         m = run_workload("million", max(10, args.steps // 2), max(3, args.warmup // 4), False)

@@ -148,7 +148,9 @@ ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
 
 /*
  * The whole path: ta_decode_partial with P = ta_suggest_chunks(p) equal
- * chunks into `workspace`, then ta_tree_combine.
+ * chunks into `workspace`, then ta_tree_combine.  When P = 1 (short contexts
+ * in a large batch) the single chunk is the result: the streaming kernel
+ * normalises and stores out / lse itself and no second kernel is launched.
  *   workspace        device scratch, 256-byte aligned, at least
  *                    ta_workspace_bytes(p, ta_suggest_chunks(p)) bytes;
  *                    contents undefined before and after.

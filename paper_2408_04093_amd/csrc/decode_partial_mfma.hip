@@ -106,6 +106,18 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     // virtual head of a row: token-major [Sq][Hq]
     auto vhead = [&](int row) { return (t0 + row / g) * a.Hq + hk * g + row % g; };
 
+    const bool direct = a.lse_out != nullptr;   // P == 1: write the final result, not a partial
+    if (n <= 0 && direct) {   // no key at all: out = 0, lse = -inf by definition
+        if constexpr (MODE == kFull) {
+            for (int i = tid; i < nrows * D; i += kThreads) {
+                const int64_t o = ((int64_t)b * HqV + vhead(i / D)) * D + (i % D);
+                if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[o] = 0;
+                else reinterpret_cast<float *>(a.out)[o] = 0.f;
+            }
+        }
+        if (tid < nrows) a.lse_out[(int64_t)b * HqV + vhead(tid)] = -__builtin_huge_valf();
+        return;
+    }
     if (n <= 0) {   // empty chunk: the identity of the merge
         if constexpr (MODE != kEnergy) {
             for (int i = tid; i < nrows * D; i += kThreads)
@@ -377,8 +389,17 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                 float ms = lds_m[0][h];
 #pragma unroll
                 for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
-                const int64_t pidx = ((int64_t)b * HqV + vhead(16 * rb + h)) * a.P + chunk;
+                const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
+                const int64_t pidx = vrow * a.P + chunk;
                 if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
+                    if (direct) {
+                        if constexpr (MODE == kFull) {
+                            if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[vrow * D + col] = 0;
+                            else reinterpret_cast<float *>(a.out)[vrow * D + col] = 0.f;
+                        }
+                        if (col == 0) a.lse_out[vrow] = ms;
+                        continue;
+                    }
                     if constexpr (MODE == kFull) a.part_o[pidx * D + col] = 0.f;
                     if (col == 0) {
                         a.part_m[pidx] = ms;
@@ -393,6 +414,15 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                     const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
                     lt = fmaf(f, lds_l[ww][h], lt);
                     if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * 16 + h) * D + col], ot);
+                }
+                if (direct) {   // single chunk: Algorithm 3 step 6 right here
+                    if constexpr (MODE == kFull) {
+                        const float z = ot / lt;
+                        if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[vrow * D + col] = f32_to_bf16_rne(z);
+                        else reinterpret_cast<float *>(a.out)[vrow * D + col] = z;
+                    }
+                    if (col == 0) a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
+                    continue;
                 }
                 // natural-log units for the stored max; l and o follow the rounding of the stored value
                 const float m_nat = ms * (float)kLn2;

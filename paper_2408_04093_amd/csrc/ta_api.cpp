@@ -134,7 +134,8 @@ size_t workspace_bytes(const ta_problem *p, int32_t P) {
 // the matrix-core kernel only.
 ta_status run_partial(const ta_problem *p, const void *q, const void *K, const void *V, int32_t P,
                       const int64_t *chunk_bounds, float *part_m, float *part_l, float *part_o,
-                      const float *lse_in, int mode, void *stream) {
+                      const float *lse_in, int mode, void *stream,
+                      void *direct_out = nullptr, float *direct_lse = nullptr) {
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || (mode != 1 && !V)) return TA_ERR_NULL;
@@ -152,6 +153,7 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     a.bounds = chunk_bounds;
     a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
     a.lse_in = lse_in;
+    a.out = direct_out; a.lse_out = direct_lse; a.out_dtype = p->out_dtype;
     a.N = p->N;
     a.t = (p->N + P - 1) / P;
     a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
@@ -231,10 +233,15 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || !V || !workspace || !out || !lse) return TA_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
 
+    if (P == 1 && use_mfma_path(p->qkv_dtype, p->d)) {
+        // one chunk per sequence: the streaming kernel normalises and writes out / lse itself
+        if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
+        return run_partial(p, q, K, V, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 0, stream, out, lse);
+    }
     // workspace layout: part_o [B,Hq,P,d] | part_m [B,Hq,P] | part_l [B,Hq,P]
     const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;
     float *part_o = static_cast<float *>(workspace);
@@ -251,9 +258,11 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || !workspace || !lse) return TA_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return TA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
+    if (P == 1)
+        return run_partial(p, q, K, nullptr, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 1, stream, nullptr, lse);
     const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;
     float *part_m = static_cast<float *>(workspace) + bhp * p->d;      // same slots as in ta_decode
     float *part_l = part_m + bhp;

@@ -17,6 +17,11 @@ struct PartialArgs {
     const int64_t *bounds;      // device [P+1] or null
     float *part_m, *part_l, *part_o;
     const float *lse_in;        // gradient pass only: total logsumexp per (b, token, head)
+    // P == 1 shortcut (matrix-core kernel): the single chunk IS the result, written here directly
+    // (normalised out, natural-log lse) instead of a partial; null = write partials
+    void *out;
+    float *lse_out;
+    int32_t out_dtype;
     int64_t N;
     int64_t t;                  // keys per chunk when bounds == null
     int64_t k_sb, k_sh, v_sb, v_sh;   // elements

@@ -576,3 +576,25 @@ def test_energy_llama_128k_full():
     torch.cuda.synchronize()
     assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
     assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+
+
+def test_batched_short_contexts_take_the_single_chunk_path():
+    """64 sequences x 4 kv heads = one workgroup per CU with P = 1: out and lse come straight from
+    the streaming kernel (no partials, no combine launch)."""
+    w = W.make_qkv(64, 8, 4, 128, 3000, torch.bfloat16, seed=71, device="cuda")
+    p = ta.make_problem(w.q, w.K, w.V, w.scale)
+    assert ta.ta_suggest_chunks(p) == 1
+    check(w)
+    g = torch.Generator().manual_seed(3)
+    w.valid_len = torch.randint(0, 3001, (64,), generator=g, dtype=torch.int32).cuda()
+    w.valid_len[5] = 0
+    p = ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len)
+    assert ta.ta_suggest_chunks(p) == 1
+    out, lse = check(w)
+    assert not out[5].any() and np.isneginf(lse[5]).all()
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    torch.cuda.synchronize()
+    assert lse_err(lse_e.cpu().numpy(), lse.astype(np.float64)) <= 1e-5
+    wm = W.make_multi(64, 3, 8, 4, 128, 500, torch.bfloat16, seed=72, device="cuda")
+    assert ta.ta_suggest_chunks(ta.make_problem(wm.q, wm.K, wm.V, wm.scale)) == 1
+    check_multi(wm)
