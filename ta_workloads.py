@@ -142,7 +142,7 @@ def combine_stress(N=262144, P=64, device="cpu", B=4, Hq=64, Hkv=8, d=128):
 
 def paper_shard(N=80000, device="cpu"):
     w = make_qkv(1, 16, 16, 128, N, torch.bfloat16, BASE_SEED + 5, device, scale=1.0, name=f"shard{N}")
-    # with scale 1 and unit-variance q the scores have std ~11 and the softmax is one-hot;
+    # with scale 1 and unit-variance q the scores have std ~11 and all weight lands on one key;
     # q carries the 1/sqrt(d) instead
     w.q = (w.q.float() * (128 ** -0.5)).to(torch.bfloat16)
     return w
