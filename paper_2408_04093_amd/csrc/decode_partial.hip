@@ -1,5 +1,7 @@
-// decode_partial: per-chunk partial softmax statistics (m, l, o) for one query
-// token, all heads of a GQA group at once.  Tree Attention (arXiv 2408.04093)
+// decode_partial, vector-ALU form: per-chunk partial softmax statistics
+// (m, l, o) for one query token, all heads of a GQA group at once.  This kernel
+// serves fp32 K/V and d = 64; bf16 with d = 128 runs on the matrix-core kernel
+// in decode_partial_mfma.hip.  Tree Attention (arXiv 2408.04093)
 // Algorithm 3 steps 1-2 with the chunks mapped to workgroups of one gfx950 GPU
 // instead of devices; inside a chunk it is the running-max form of the
 // Section 3 recurrence (n_i = n_{i-1} + v_i s_i, d_i = d_{i-1} + s_i) made safe
