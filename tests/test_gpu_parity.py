@@ -598,3 +598,23 @@ def test_batched_short_contexts_take_the_single_chunk_path():
     wm = W.make_multi(64, 3, 8, 4, 128, 500, torch.bfloat16, seed=72, device="cuda")
     assert ta.ta_suggest_chunks(ta.make_problem(wm.q, wm.K, wm.V, wm.scale)) == 1
     check_multi(wm)
+
+
+def test_largest_supported_head_slice():
+    """One [N, d] head slice just under the 4 GiB limit of the 32-bit row offsets (N = 2^24 - 8 keys)."""
+    N = (1 << 24) - 8
+    w = W.make_qkv(1, 2, 1, 128, N, torch.bfloat16, seed=91, device="cuda")
+    p = ta.make_problem(w.q, w.K, w.V, w.scale)
+    assert ta.ta_suggest_chunks(p) > 0
+    p.N = 1 << 24                                  # one row more would need a 33-bit offset: refused on the host
+    assert ta.ta_suggest_chunks(p) == 0
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    # the last rows really are read: poison the final key and the result must change
+    w.K[0, 0, N - 1] = 40.0
+    out2, lse2 = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
+    assert not torch.equal(lse, lse2)
