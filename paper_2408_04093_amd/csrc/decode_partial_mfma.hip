@@ -238,44 +238,62 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
             *reinterpret_cast<v4i *>(stage + trow[e] * kPitch + c * 16) = kr[e];
         if (it + TA_DEPTH < n_iters) issue_k(kr, it + TA_DEPTH);
 
-        f32x4 s[NRB][2];
+        // S = K Q^T.  The 2 key groups x NRB row blocks are independent accumulation chains; the
+        // k-step loop is outermost so that consecutive MFMAs never depend on each other.
+        v4i af[2][4];
 #pragma unroll
-        for (int G = 0; G < 2; ++G) {
-            v4i af[4];
+        for (int G = 0; G < 2; ++G)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                af[t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
+                af[G][t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
+        f32x4 s[NRB][2];
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) {
-                s[rb][G] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int rb = 0; rb < NRB; ++rb) s[rb][0] = s[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), qb[rb][t],
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int G = 0; G < 2; ++G)
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb)
+                    s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[G][t]), qb[rb][t],
                                                                         s[rb][G], 0, 0, 0);
-            }
-        }
 
-        // ---- online softmax: per row block this lane owns 8 keys (slot e = 4G + i) of one row
-        bf16x8 pa_hi[NRB], pa_lo[NRB];
+        // ---- online softmax: per row block this lane owns 8 keys (slot e = 4G + i) of one row.
+        // Done in phases over all row blocks (scores and row max; one shared decision whether any
+        // running max must be raised; exponentials) so that the blocks' dependency chains interleave.
+        float sv[NRB][8];
+        bool up[NRB];
+        float mx[NRB];
+        bool any_up = false;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
-            float sv[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                sv[e] = s[rb][e >> 2][e & 3] * cs;
-                if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[e] = -__builtin_huge_valf();
+                sv[rb][e] = s[rb][e >> 2][e & 3] * cs;
+                if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[rb][e] = -__builtin_huge_valf();
             }
             if constexpr (MODE != kGradient) {
-                float mx = sv[0];
+                float m8 = sv[rb][0];
 #pragma unroll
-                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sv[e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const bool up = mx > m_run[rb];
-                if (__builtin_amdgcn_ballot_w64(up) != 0) {
-                    // raise the running max: rare once the stream is warm
-                    const float alpha = up ? exp2_hw(m_run[rb] - mx) : 1.0f;
-                    m_run[rb] = up ? mx : m_run[rb];
+                for (int e = 1; e < 8; ++e) m8 = fmaxf(m8, sv[rb][e]);
+                mx[rb] = m8;
+            }
+        }
+        if constexpr (MODE != kGradient) {
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 16));
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) {
+                mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 32));
+                up[rb] = mx[rb] > m_run[rb];
+                any_up |= up[rb];
+            }
+            if (__builtin_amdgcn_ballot_w64(any_up) != 0) {
+                // raise running maxima: rare once the stream is warm
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) {
+                    const float alpha = up[rb] ? exp2_hw(m_run[rb] - mx[rb]) : 1.0f;
+                    m_run[rb] = up[rb] ? mx[rb] : m_run[rb];
                     l_run[rb] *= alpha;
                     if constexpr (MODE == kFull) {
                         // acc[rb][.][i] belongs to row 4r+i of the block, whose alpha sits in lane (r, 4r+i)
@@ -288,11 +306,15 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                     }
                 }
             }
+        }
+        bf16x8 pa_hi[NRB], pa_lo[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
             float p[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                p[e] = exp2_hw(sv[e] - m_run[rb]);
-                if (masked && sv[e] == -__builtin_huge_valf()) p[e] = 0.f;
+                p[e] = exp2_hw(sv[rb][e] - m_run[rb]);
+                if (masked && sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;
                 l_run[rb] += p[e];
             }
             if constexpr (MODE != kEnergy) {
@@ -322,10 +344,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                 }
                 const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
 #pragma unroll
-                for (int rb = 0; rb < NRB; ++rb) {
+                for (int rb = 0; rb < NRB; ++rb)
                     acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi[rb], vbj, acc[rb][j], 0, 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb)
                     acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo[rb], vbj, acc[rb][j], 0, 0, 0);
-                }
             }
             if (it + TA_DEPTH < n_iters) issue_v(vr, it + TA_DEPTH);
         }
