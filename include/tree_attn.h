@@ -100,10 +100,13 @@ typedef struct ta_problem {
 const char *ta_status_string(ta_status s);
 
 /*
- * Chunk count P that ta_decode uses for this problem on the current device
- * (host-only heuristic: enough workgroups to fill every compute unit several
- * times over, chunks no shorter than a few hundred keys).  Returns 0 if the
- * problem is invalid.
+ * Chunk count P that ta_decode uses for this problem on the current device.
+ * Host-only heuristic: with equal work per chunk, one workgroup per compute
+ * unit (P = CUs / (B * Hkv), more rounds only beyond 32768 keys per chunk);
+ * for ragged batches or more (batch, kv head) groups than compute units,
+ * chunks of a few thousand keys; never shorter than 256 keys; 1 when one
+ * chunk per sequence already fills the device.  Returns 0 if the problem is
+ * invalid.
  */
 int32_t ta_suggest_chunks(const ta_problem *p);
 
