@@ -191,6 +191,10 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"
     if op != "decode":
         # the energy / gradient passes are the same streaming kernel in another mode: report the whole step
         kernel_name, us_partial, ach, tr = f"{op}: streaming passes + combine", ms_per_step * 1e3, gbps, None
+    elif w0.valid_len is not None:
+        # ragged batches run the balanced launch inside ta_decode, which ta_decode_partial does not
+        # expose: report the whole step (balanced streaming kernel + combine)
+        kernel_name, us_partial, ach, tr = "decode_balanced + combine (whole step)", ms_per_step * 1e3, gbps, None
 
     result = {
         "metric": "decode_attention_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",

@@ -79,34 +79,44 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
 // K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
 enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 
-template <int MODE, int NRB>
-__global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
-    __shared__ float lds_m[kWaves][kMaxHeads];
-    __shared__ float lds_l[kWaves][kMaxHeads];
+// Where one range of keys of one (batch, kv head, token slice) goes.
+struct Range {
+    int b, hk, slice;
+    int64_t lo;     // first key
+    int n;          // number of keys
+    int64_t L;      // valid length of the sequence (causal limits among query tokens)
+    int64_t slot;   // chunked launch: chunk index; balanced launch: piece id
+};
 
+// The whole streaming computation for one range: called once per workgroup by the chunked kernel
+// and once per piece by the balanced kernel.  smem / lds_m / lds_l are the workgroup's LDS areas.
+template <int MODE, int NRB, bool BALANCED>
+__device__ __forceinline__ void process_range(const PartialArgs &a, const Range &rg, char *smem,
+                                              float (*lds_m)[kMaxHeads], float (*lds_l)[kMaxHeads]) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane >> 4, c = lane & 15;     // row group / (column block or row within a row block)
     const int g = a.g;                          // heads of the group, all in this workgroup
-
-    __shared__ int sh_rank[kMaxRankedChunks + 1];
-    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
-    const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
-    const int64_t lo = cr.lo;
-    const int n = cr.n;
+    const int hk = rg.hk, b = rg.b;
+    const int64_t lo = rg.lo;
+    const int n = rg.n;
 
     // MFMA rows: row = (local token) * g + (head in group); this workgroup owns
     // query tokens [t0, t0 + ntok) of the Sq (one token in plain decode)
-    const int t0 = cr.slice * a.tq;
+    const int t0 = rg.slice * a.tq;
     const int ntok = (a.Sq - t0) < a.tq ? (a.Sq - t0) : a.tq;
     const int nrows = ntok * g;                 // <= 16 * NRB
     const int HqV = a.Sq * a.Hq;                // (token, head) pairs per sequence
     // virtual head of a row: token-major [Sq][Hq]
     auto vhead = [&](int row) { return (t0 + row / g) * a.Hq + hk * g + row % g; };
+    // index of a row's partial: [B, Sq*Hq, P] in a chunked launch, [piece, piece_rows] in a balanced one
+    auto pindex = [&](int row) -> int64_t {
+        if constexpr (BALANCED) return rg.slot * a.piece_rows + row;
+        else return ((int64_t)b * HqV + vhead(row)) * a.P + rg.slot;
+    };
 
-    const bool direct = a.lse_out != nullptr;   // P == 1: write the final result, not a partial
+    const bool direct = !BALANCED && a.lse_out != nullptr;   // P == 1: write the final result, not a partial
     if (n <= 0 && direct) {   // no key at all: out = 0, lse = -inf by definition
         if constexpr (MODE == kFull) {
             for (int i = tid; i < nrows * D; i += kThreads) {
@@ -121,11 +131,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     if (n <= 0) {   // empty chunk: the identity of the merge
         if constexpr (MODE != kEnergy) {
             for (int i = tid; i < nrows * D; i += kThreads)
-                a.part_o[(((int64_t)b * HqV + vhead(i / D)) * a.P + chunk) * D + (i % D)] = 0.f;
+                a.part_o[pindex(i / D) * D + (i % D)] = 0.f;
         }
         if constexpr (MODE != kGradient) {
             if (tid < nrows) {
-                const int64_t pi = ((int64_t)b * HqV + vhead(tid)) * a.P + chunk;
+                const int64_t pi = pindex(tid);
                 a.part_m[pi] = -__builtin_huge_valf();
                 a.part_l[pi] = 0.f;
             }
@@ -142,7 +152,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     for (int rb = 0; rb < NRB; ++rb) {
         const int row = 16 * rb + c;
         my_row[rb] = row < nrows ? row : 0;
-        const int64_t lim = cr.L - a.Sq + 1 + (t0 + my_row[rb] / g) - lo;
+        const int64_t lim = rg.L - a.Sq + 1 + (t0 + my_row[rb] / g) - lo;
         nlim[rb] = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
         const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row[rb])) * D + 8 * r) * 2;
 #pragma unroll
@@ -154,7 +164,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     }
     int n_common;   // keys every row may use: steps below it need no masking
     {
-        const int64_t limc = cr.L - a.Sq + 1 + t0 - lo;
+        const int64_t limc = rg.L - a.Sq + 1 + t0 - lo;
         n_common = (int)(limc < 0 ? 0 : (limc > n ? n : limc));
     }
 
@@ -404,7 +414,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
                 float ot = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww) ot += lds_o[(ww * 16 + h) * D + col];
-                a.part_o[(((int64_t)b * HqV + vhead(16 * rb + h)) * a.P + chunk) * D + col] = ot;
+                a.part_o[pindex(16 * rb + h) * D + col] = ot;
             }
         } else {
             const int col = MODE == kEnergy ? 0 : tid % D;
@@ -413,7 +423,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 #pragma unroll
                 for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
                 const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
-                const int64_t pidx = vrow * a.P + chunk;
+                const int64_t pidx = pindex(16 * rb + h);
                 if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
                     if (direct) {
                         if constexpr (MODE == kFull) {
@@ -460,6 +470,116 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
     }
 }
 
+// Chunked launch: one workgroup per (batch, kv head, token slice, chunk).
+template <int MODE, int NRB>
+__global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
+    __shared__ float lds_m[kWaves][kMaxHeads];
+    __shared__ float lds_l[kWaves][kMaxHeads];
+    __shared__ int sh_rank[kMaxRankedChunks + 1];
+    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
+    process_range<MODE, NRB, false>(a, rg, smem, lds_m, lds_l);
+}
+
+// Balanced launch for ragged batches (lengths known only on the device).  The keys of all
+// (batch, kv head, token slice) segments are laid end to end and cut into W equal shares, one per
+// workgroup (W = compute units), so every workgroup streams the same number of bytes whatever the
+// mix of lengths; a share that crosses a segment boundary is processed as several pieces.  Piece
+// ids (workgroup index + segment index) are unique and the pieces of one segment are consecutive,
+// which is all the combine kernel needs.  Associativity (Section 5.1) makes the cut points free.
+//
+// Shares are equal in COST, not in keys: every non-empty segment is charged kPieceCost extra
+// "virtual keys" at its start for the fixed cost of a piece (q load, pipeline ramp, epilogue: ~3 us,
+// the time a CU streams ~200 keys), so a workgroup that gets a run of tiny sequences gets fewer of
+// them.  Without the charge a share made of ~100 tiny segments took 2x the time of the others.
+constexpr int kMaxBalancedB = 2048;   // sequences whose prefix sums fit the LDS table
+constexpr int kMinShare = 512;        // virtual keys: never cut finer than this
+constexpr int kPieceCost = 256;       // virtual keys charged per non-empty segment
+
+template <int NRB>
+__global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const PartialArgs a) {
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
+    __shared__ float lds_m[kWaves][kMaxHeads];
+    __shared__ float lds_l[kWaves][kMaxHeads];
+    __shared__ int64_t sh_cum[kMaxBalancedB + 1];
+    __shared__ int64_t sh_scan[kThreads];
+
+    const int tid = threadIdx.x;
+    auto len_of = [&](int bb) -> int64_t {   // virtual length of one segment of sequence bb
+        int64_t L = a.N;
+        if (a.valid_len) {
+            L = a.valid_len[bb];
+            L = L < 0 ? 0 : (L > a.N ? a.N : L);
+        }
+        return L > 0 ? L + kPieceCost : 0;
+    };
+    // exclusive prefix sums of the virtual lengths: each thread takes a run of sequences, then a
+    // 256-wide scan of the run totals
+    const int per = (a.B + kThreads - 1) / kThreads;
+    int64_t mine = 0;
+    for (int i = 0; i < per; ++i) {
+        const int bb = tid * per + i;
+        if (bb < a.B) mine += len_of(bb);
+    }
+    sh_scan[tid] = mine;
+    __syncthreads();
+    for (int off = 1; off < kThreads; off <<= 1) {
+        const int64_t v = tid >= off ? sh_scan[tid - off] : 0;
+        __syncthreads();
+        sh_scan[tid] += v;
+        __syncthreads();
+    }
+    int64_t run = sh_scan[tid] - mine;
+    for (int i = 0; i < per; ++i) {
+        const int bb = tid * per + i;
+        if (bb < a.B) {
+            sh_cum[bb] = run;
+            run += len_of(bb);
+        }
+    }
+    if (tid == 0) sh_cum[a.B] = sh_scan[kThreads - 1];
+    __syncthreads();
+    if (blockIdx.x == 0)   // the combine kernel reads the same table
+        for (int i = tid; i <= a.B; i += kThreads) a.cum[i] = sh_cum[i];
+
+    const int64_t G = (int64_t)a.Hkv * a.slices;
+    const int64_t T = sh_cum[a.B] * G;
+    int64_t S = (T + a.W - 1) / a.W;
+    S = S < kMinShare ? kMinShare : S;
+    const int64_t x0 = (int64_t)blockIdx.x * S;
+    const int64_t x1 = x0 + S < T ? x0 + S : T;
+    if (x0 >= T) return;
+
+    int b = 0, hi_b = a.B;   // cum[b] * G <= x0 < cum[hi_b] * G
+    while (hi_b - b > 1) {
+        const int mid = (b + hi_b) >> 1;
+        if (sh_cum[mid] * G <= x0) b = mid; else hi_b = mid;
+    }
+    bool first = true;
+    for (int64_t x = x0; x < x1;) {
+        while (sh_cum[b + 1] * G <= x) ++b;        // also skips empty sequences; b < B because x < T
+        const int64_t Lv = sh_cum[b + 1] - sh_cum[b];   // virtual length of this sequence's segments
+        const int64_t Lb = Lv - kPieceCost;             // its keys
+        const int64_t rel = x - sh_cum[b] * G;
+        const int64_t j = rel / Lv;                // (kv head, token slice) of this sequence
+        const int64_t v0 = rel - j * Lv;           // virtual offset inside the segment
+        const int64_t span = (Lv - v0) < (x1 - x) ? (Lv - v0) : (x1 - x);
+        // the first kPieceCost virtual keys of a segment are the charge, the rest are its keys
+        const int64_t k0 = v0 > kPieceCost ? v0 - kPieceCost : 0;
+        int64_t k1 = v0 + span - kPieceCost;
+        k1 = k1 > Lb ? Lb : k1;
+        if (k1 > k0) {
+            const Range rg{b, (int)(j / a.slices), (int)(j % a.slices), k0, (int)(k1 - k0), Lb,
+                           (int64_t)blockIdx.x + (int64_t)b * G + j};
+            if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
+            first = false;
+            process_range<kFull, NRB, true>(a, rg, smem, lds_m, lds_l);
+        }
+        x += span;
+    }
+}
+
 }  // namespace
 
 template <int NRB>
@@ -479,6 +599,19 @@ hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_
     if (rows <= 32) return launch_mode<2>(a, mode, grid, s);
     return launch_mode<4>(a, mode, grid, s);
 }
+
+hipError_t launch_decode_balanced_mfma(const PartialArgs &a, hipStream_t s) {
+    const dim3 grid((uint32_t)a.W);
+    const int rows = a.tq * a.g;
+    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<1>), grid, dim3(kThreads), 0, s, a);
+    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<2>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<4>), grid, dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+int balanced_max_batch() { return kMaxBalancedB; }
+int balanced_min_share() { return kMinShare; }
+int balanced_piece_cost() { return kPieceCost; }
 
 int decode_partial_mfma_occupancy() {
     static const int cached = [] {

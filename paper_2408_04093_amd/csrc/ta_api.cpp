@@ -124,9 +124,41 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     return (int32_t)P;
 }
 
+// Ragged batches on the matrix-core kernel run the balanced launch: every workgroup gets an equal
+// share of all keys (see decode_balanced_mfma_kernel).
+inline bool use_balanced(const ta_problem *p) {
+    return p->valid_len != nullptr && use_mfma_path(p->qkv_dtype, p->d) && p->B <= balanced_max_batch();
+}
+
+struct BalancedPlan {
+    int32_t W;           // workgroups
+    int64_t pieces;      // upper bound on piece ids: W + number of segments
+    int32_t rows;        // rows reserved per piece
+    size_t off_m, off_l, off_cum, bytes;   // byte offsets in the workspace (part_o at 0)
+};
+
+BalancedPlan balanced_plan(const ta_problem *p, int cus) {
+    BalancedPlan b{};
+    const int64_t groups = launch_groups(p);
+    b.W = cus;
+    b.pieces = b.W + groups;
+    b.rows = tokens_per_workgroup(p) * (p->Hq / p->Hkv);
+    const size_t slots = (size_t)b.pieces * b.rows;
+    b.off_m = slots * p->d * sizeof(float);
+    b.off_l = b.off_m + slots * sizeof(float);
+    b.off_cum = (b.off_l + slots * sizeof(float) + 7) & ~(size_t)7;
+    b.bytes = (b.off_cum + ((size_t)p->B + 1) * sizeof(int64_t) + 255) & ~(size_t)255;
+    return b;
+}
+
 size_t workspace_bytes(const ta_problem *p, int32_t P) {
     const size_t floats = (size_t)p->B * tokens(p) * p->Hq * (size_t)P * (size_t)(p->d + 2);
-    return (floats * sizeof(float) + 255) & ~(size_t)255;
+    size_t bytes = (floats * sizeof(float) + 255) & ~(size_t)255;
+    if (use_balanced(p)) {
+        const size_t need = balanced_plan(p, device_compute_units()).bytes;
+        if (need > bytes) bytes = need;
+    }
+    return bytes;
 }
 
 // Validate and launch one pass over the chunks.  mode: 0 = (m,l,o); 1 = energy pass (K only; V and
@@ -237,6 +269,44 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
 
+    if (use_balanced(p)) {
+        // ragged batch: equal shares of all keys per workgroup, then the combine over each row's pieces
+        if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TA_ERR_ALIGN;
+        if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
+        const BalancedPlan bp = balanced_plan(p, device_compute_units());
+        char *base = static_cast<char *>(workspace);
+        const int eb = elem_bytes(p->qkv_dtype);
+        PartialArgs a{};
+        a.q = q; a.K = K; a.V = V;
+        a.valid_len = p->valid_len;
+        a.part_o = reinterpret_cast<float *>(base);
+        a.part_m = reinterpret_cast<float *>(base + bp.off_m);
+        a.part_l = reinterpret_cast<float *>(base + bp.off_l);
+        a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
+        a.N = p->N;
+        a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
+        a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
+        a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
+        a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
+        a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = 1;
+        a.g = p->Hq / p->Hkv;
+        a.Sq = tokens(p);
+        a.tq = tokens_per_workgroup(p);
+        a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
+        a.c = (double)p->scale * kLog2e;
+        a.W = bp.W;
+        a.piece_rows = bp.rows;
+        if (launch_decode_balanced_mfma(a, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
+        CombineArgs c{};
+        c.part_m = a.part_m; c.part_l = a.part_l; c.part_o = a.part_o;
+        c.out = out; c.lse = lse;
+        c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = 0;
+        c.out_dtype = p->out_dtype;
+        c.cum = a.cum;
+        c.W = bp.W; c.min_share = balanced_min_share(); c.piece_cost = balanced_piece_cost(); c.piece_rows = bp.rows;
+        c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.tq = a.tq;
+        return launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
+    }
     if (P == 1 && use_mfma_path(p->qkv_dtype, p->d)) {
         // one chunk per sequence: the streaming kernel normalises and writes out / lse itself
         if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;

@@ -22,6 +22,11 @@ struct PartialArgs {
     void *out;
     float *lse_out;
     int32_t out_dtype;
+    // balanced launch (matrix-core kernel, ragged batches): W workgroups share all keys equally
+    int32_t W;                  // workgroups = shares
+    int32_t piece_rows;         // rows reserved per piece in the partial arrays (tq * g)
+    int64_t *cum;               // device [B+1]: prefix sums of the virtual lengths (keys + piece charge),
+                                // written by workgroup 0 for the combine kernel
     int64_t N;
     int64_t t;                  // keys per chunk when bounds == null
     int64_t k_sb, k_sh, v_sb, v_sh;   // elements
@@ -38,8 +43,12 @@ struct CombineArgs {
     const float *part_m, *part_l, *part_o;
     void *out;
     float *lse;
-    int32_t B, Hq, P;
+    int32_t B, Hq, P;           // Hq counts (token, head) rows per sequence
     int32_t out_dtype;
+    // balanced launch: the partials of row (b, t, h) are the consecutive pieces of its segment
+    const int64_t *cum;         // null = chunked layout [B,Hq,P]
+    int32_t W, min_share, piece_cost, piece_rows;
+    int32_t heads, g, Hkv, slices, tq;   // real Hq, group size, kv heads, token slices, tokens per slice
 };
 // energy pass: lse from (m, l) partials only; gradient pass: out = plain sum of the partial numerators
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s);
@@ -62,6 +71,10 @@ int decode_partial_occupancy(int dtype, int d, int gt);
 // bf16, d = 128.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)
 hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s);
 int decode_partial_mfma_occupancy();
+hipError_t launch_decode_balanced_mfma(const PartialArgs &a, hipStream_t s);
+int balanced_max_batch();
+int balanced_min_share();
+int balanced_piece_cost();
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 
 }  // namespace ta

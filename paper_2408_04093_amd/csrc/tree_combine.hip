@@ -52,10 +52,37 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
     const int r = tid / kSlice;
     const int64_t bh = blockIdx.x / kSlices;
     const int col = (blockIdx.x % kSlices) * kSlice + c;
-    const int P = a.P;
+    // where this row's partials live: [B,Hq,P] (chunked launch) or the consecutive pieces of the
+    // row's segment, piece_rows apart (balanced launch)
+    int P = a.P;
+    int64_t sm = 1, so = D;                      // strides between consecutive partials
     const float *pm = a.part_m + bh * P;
     const float *pl = a.part_l + bh * P;
     const float *po = a.part_o + bh * P * D + col;
+    if (a.cum) {
+        const int b = (int)(bh / a.Hq), vrow = (int)(bh % a.Hq);
+        const int t = vrow / a.heads, hq = vrow % a.heads;
+        const int row = (t % a.tq) * a.g + hq % a.g;
+        const int64_t G = (int64_t)a.Hkv * a.slices;
+        const int64_t j = (int64_t)(hq / a.g) * a.slices + t / a.tq;
+        // cum holds virtual lengths: keys + piece_cost per non-empty segment, the keys coming last
+        const int64_t Lv = a.cum[b + 1] - a.cum[b];
+        const int64_t Lb = Lv - a.piece_cost;
+        int64_t S = (a.cum[a.B] * G + a.W - 1) / a.W;
+        S = S < a.min_share ? a.min_share : S;
+        P = 0;
+        if (Lv > 0) {
+            const int64_t seg0 = a.cum[b] * G + j * Lv + a.piece_cost;   // first key, virtual position
+            const int64_t w0 = seg0 / S, w1 = (seg0 + Lb - 1) / S;
+            const int64_t id0 = w0 + (int64_t)b * G + j;
+            P = (int)(w1 - w0 + 1);
+            sm = a.piece_rows;
+            so = (int64_t)a.piece_rows * D;
+            pm = a.part_m + id0 * a.piece_rows + row;
+            pl = a.part_l + id0 * a.piece_rows + row;
+            po = a.part_o + (id0 * a.piece_rows + row) * D + col;
+        }
+    }
 
     __shared__ float sh_red[kWaves];
     __shared__ float sh_w[kTile];
@@ -66,13 +93,13 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
         const int j = r + i * kGroups;
-        x0[i] = j < P ? po[(int64_t)j * D] : 0.f;
+        x0[i] = j < P ? po[(int64_t)j * so] : 0.f;
     }
 
     // m* = max over partials that hold keys (l_j > 0)
     float mx = -__builtin_huge_valf();
     for (int j = tid; j < P; j += kThreads)
-        if (pl[j] > 0.f) mx = fmaxf(mx, pm[j]);
+        if (pl[j * sm] > 0.f) mx = fmaxf(mx, pm[j * sm]);
     const float mstar = block_reduce(mx, sh_red, true);
 
     if (mstar == -__builtin_huge_valf()) {   // no key anywhere: out = 0, lse = -inf by definition
@@ -89,8 +116,8 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
         const int tn = P - t0 < kTile ? P - t0 : kTile;
         if (t0) __syncthreads();
         for (int j = tid; j < tn; j += kThreads) {
-            const float lj = pl[t0 + j];
-            const float wj = lj > 0.f ? exp2_hw((pm[t0 + j] - mstar) * kLog2eF) : 0.f;
+            const float lj = pl[(t0 + j) * sm];
+            const float wj = lj > 0.f ? exp2_hw((pm[(t0 + j) * sm] - mstar) * kLog2eF) : 0.f;
             sh_w[j] = wj;
             lsum = fmaf(wj, lj, lsum);
         }
@@ -104,7 +131,7 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
 #pragma unroll
                 for (int i = 0; i < kBatch; ++i) {
                     const int j = j0 + i * kGroups;
-                    x[i] = j < tn ? po[(int64_t)(t0 + j) * D] : 0.f;
+                    x[i] = j < tn ? po[(int64_t)(t0 + j) * so] : 0.f;
                 }
             }
 #pragma unroll

@@ -618,3 +618,35 @@ def test_largest_supported_head_slice():
     out2, lse2 = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
     torch.cuda.synchronize()
     assert not torch.equal(lse, lse2)
+
+
+def test_skewed_ragged_batch_is_balanced_over_the_device():
+    """One long sequence among many short and empty ones: the balanced launch cuts all keys into
+    equal shares, so pieces cross sequence and head boundaries in every combination."""
+    B, N = 24, 40000
+    w = W.make_qkv(B, 8, 2, 128, N, torch.bfloat16, seed=81, device="cuda")
+    g = torch.Generator().manual_seed(8)
+    vl = torch.randint(1, 300, (B,), generator=g, dtype=torch.int32)
+    vl[3] = N; vl[0] = 0; vl[7] = 0; vl[23] = 0; vl[11] = 1; vl[12] = 2
+    w.valid_len = vl.cuda()
+    for b in range(B):                      # poison the padding: it must never be read
+        w.K[b, :, int(vl[b]):] = float("nan")
+        w.V[b, :, int(vl[b]):] = float("nan")
+    out, lse = check(w)
+    assert not out[0].any() and np.isneginf(lse[[0, 7, 23]]).all()
+    # several query tokens through the same path (token slices become extra segments)
+    wm = W.make_multi(6, 5, 16, 2, 128, 9000, torch.bfloat16, seed=82, device="cuda")   # 5 x 8 = 40 rows
+    wm.valid_len = torch.tensor([9000, 3, 0, 700, 5, 4321], dtype=torch.int32, device="cuda")
+    check_multi(wm)
+    wm = W.make_multi(3, 9, 16, 1, 128, 2000, torch.bfloat16, seed=83, device="cuda")   # g = 16: 4 + 4 + 1 tokens
+    wm.valid_len = torch.tensor([2000, 8, 1234], dtype=torch.int32, device="cuda")
+    check_multi(wm)
+
+
+def test_very_large_ragged_batch_falls_back_to_chunks():
+    """More sequences than the balanced launch tabulates (2048): fixed-size chunks instead."""
+    B = 2100
+    w = W.make_qkv(B, 4, 1, 128, 96, torch.bfloat16, seed=84, device="cuda")
+    g = torch.Generator().manual_seed(9)
+    w.valid_len = torch.randint(0, 97, (B,), generator=g, dtype=torch.int32).cuda()
+    check(w)
