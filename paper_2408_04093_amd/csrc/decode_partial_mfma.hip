@@ -503,7 +503,7 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
     __shared__ float lds_m[kWaves][kMaxHeads];
     __shared__ float lds_l[kWaves][kMaxHeads];
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
-    __shared__ int64_t sh_scan[kThreads];
+    __shared__ int64_t sh_scan[kWaves];
 
     const int tid = threadIdx.x;
     auto len_of = [&](int bb) -> int64_t {   // virtual length of one segment of sequence bb
@@ -522,15 +522,22 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
         const int bb = tid * per + i;
         if (bb < a.B) mine += len_of(bb);
     }
-    sh_scan[tid] = mine;
-    __syncthreads();
-    for (int off = 1; off < kThreads; off <<= 1) {
-        const int64_t v = tid >= off ? sh_scan[tid - off] : 0;
+    // inclusive scan: inside each wave by shuffles, then the 4 wave totals through LDS
+    int64_t incl = mine;
+    {
+        const int lane = tid & (kWave - 1);
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int64_t v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        if (lane == kWave - 1) sh_scan[tid >> 6] = incl;
         __syncthreads();
-        sh_scan[tid] += v;
-        __syncthreads();
+        int64_t base = 0;
+        for (int ww = 0; ww < (tid >> 6); ++ww) base += sh_scan[ww];
+        incl += base;
     }
-    int64_t run = sh_scan[tid] - mine;
+    int64_t run = incl - mine;
     for (int i = 0; i < per; ++i) {
         const int bb = tid * per + i;
         if (bb < a.B) {
@@ -538,7 +545,7 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
             run += len_of(bb);
         }
     }
-    if (tid == 0) sh_cum[a.B] = sh_scan[kThreads - 1];
+    if (tid == kThreads - 1) sh_cum[a.B] = incl;
     __syncthreads();
     if (blockIdx.x == 0)   // the combine kernel reads the same table
         for (int i = tid; i <= a.B; i += kThreads) a.cum[i] = sh_cum[i];

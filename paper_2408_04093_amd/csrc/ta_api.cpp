@@ -126,8 +126,12 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
 
 // Ragged batches on the matrix-core kernel run the balanced launch: every workgroup gets an equal
 // share of all keys (see decode_balanced_mfma_kernel).
+// It pays while there are at most a few (batch, kv head) groups per compute unit: with many short
+// sequences one workgroup per sequence (several resident per CU, their start-up latencies
+// overlapping) is faster than one workgroup walking through many pieces in turn.
 inline bool use_balanced(const ta_problem *p) {
-    return p->valid_len != nullptr && use_mfma_path(p->qkv_dtype, p->d) && p->B <= balanced_max_batch();
+    return p->valid_len != nullptr && use_mfma_path(p->qkv_dtype, p->d) && p->B <= balanced_max_batch() &&
+           launch_groups(p) <= 4 * (int64_t)device_compute_units();
 }
 
 struct BalancedPlan {
