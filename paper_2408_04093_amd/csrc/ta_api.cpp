@@ -165,6 +165,31 @@ size_t workspace_bytes(const ta_problem *p, int32_t P) {
     return bytes;
 }
 
+// The launch descriptor fields that depend only on the problem and the input pointers.
+PartialArgs base_args(const ta_problem *p, const void *q, const void *K, const void *V) {
+    const int eb = elem_bytes(p->qkv_dtype);
+    PartialArgs a{};
+    a.q = q; a.K = K; a.V = V ? V : K;
+    a.valid_len = p->valid_len;
+    a.out_dtype = p->out_dtype;
+    a.N = p->N;
+    a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
+    a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
+    a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
+    a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
+    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = 1;
+    a.g = p->Hq / p->Hkv;
+    a.Sq = tokens(p);
+    a.tq = tokens_per_workgroup(p);
+    a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
+    a.c = (double)p->scale * kLog2e;
+    return a;
+}
+
+inline bool out_aligned(const void *out, int out_dtype) {
+    return (reinterpret_cast<uintptr_t>(out) & (out_dtype == TA_BF16 ? 1u : 3u)) == 0;
+}
+
 // Validate and launch one pass over the chunks.  mode: 0 = (m,l,o); 1 = energy pass (K only; V and
 // part_o unused); 2 = gradient pass given lse_in (part_m, part_l unused).  Modes 1 and 2 exist on
 // the matrix-core kernel only.
@@ -182,26 +207,13 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
          reinterpret_cast<uintptr_t>(part_o) | reinterpret_cast<uintptr_t>(lse_in)) & 3u)
         return TA_ERR_ALIGN;
 
-    const int eb = elem_bytes(p->qkv_dtype);
-    PartialArgs a{};
-    a.q = q; a.K = K; a.V = V ? V : K;
-    a.valid_len = p->valid_len;
+    PartialArgs a = base_args(p, q, K, V);
     a.bounds = chunk_bounds;
     a.part_m = part_m; a.part_l = part_l; a.part_o = part_o;
     a.lse_in = lse_in;
-    a.out = direct_out; a.lse_out = direct_lse; a.out_dtype = p->out_dtype;
-    a.N = p->N;
+    a.out = direct_out; a.lse_out = direct_lse;
+    a.P = P;
     a.t = (p->N + P - 1) / P;
-    a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
-    a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
-    a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
-    a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
-    a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = P;
-    a.g = p->Hq / p->Hkv;
-    a.Sq = tokens(p);
-    a.tq = tokens_per_workgroup(p);
-    a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
-    a.c = (double)p->scale * kLog2e;
     if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
     const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
                              ? launch_decode_partial_mfma(a, mode, static_cast<hipStream_t>(stream))
@@ -270,34 +282,19 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     if (st != TA_OK) return st;
     if (!q || !K || !V || !workspace || !out || !lse) return TA_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return TA_ERR_ALIGN;
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !out_aligned(out, p->out_dtype)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
 
     if (use_balanced(p)) {
         // ragged batch: equal shares of all keys per workgroup, then the combine over each row's pieces
-        if (!aligned16(q) || !aligned16(K) || !aligned16(V)) return TA_ERR_ALIGN;
-        if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
         const BalancedPlan bp = balanced_plan(p, device_compute_units());
         char *base = static_cast<char *>(workspace);
-        const int eb = elem_bytes(p->qkv_dtype);
-        PartialArgs a{};
-        a.q = q; a.K = K; a.V = V;
-        a.valid_len = p->valid_len;
+        PartialArgs a = base_args(p, q, K, V);
         a.part_o = reinterpret_cast<float *>(base);
         a.part_m = reinterpret_cast<float *>(base + bp.off_m);
         a.part_l = reinterpret_cast<float *>(base + bp.off_l);
         a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
-        a.N = p->N;
-        a.k_sb = p->k_stride_b; a.k_sh = p->k_stride_h;
-        a.v_sb = p->v_stride_b; a.v_sh = p->v_stride_h;
-        a.k_row_bytes = (uint32_t)(p->k_stride_n * eb);
-        a.v_row_bytes = (uint32_t)(p->v_stride_n * eb);
-        a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = 1;
-        a.g = p->Hq / p->Hkv;
-        a.Sq = tokens(p);
-        a.tq = tokens_per_workgroup(p);
-        a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
-        a.c = (double)p->scale * kLog2e;
         a.W = bp.W;
         a.piece_rows = bp.rows;
         if (launch_decode_balanced_mfma(a, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
@@ -313,7 +310,6 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     }
     if (P == 1 && use_mfma_path(p->qkv_dtype, p->d)) {
         // one chunk per sequence: the streaming kernel normalises and writes out / lse itself
-        if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
         return run_partial(p, q, K, V, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 0, stream, out, lse);
     }
     // workspace layout: part_o [B,Hq,P,d] | part_m [B,Hq,P] | part_l [B,Hq,P]
@@ -332,7 +328,9 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || !workspace || !lse) return TA_ERR_NULL;
+    if (!use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return TA_ERR_ALIGN;
+    if (!aligned16(q) || !aligned16(K)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
     if (P == 1)
@@ -352,10 +350,13 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
 ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
                              void *workspace, size_t workspace_bytes_given,
                              void *out, float *lse, void *stream) {
-    if (!V || !out) return TA_ERR_NULL;
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || !V || !workspace || !out || !lse) return TA_ERR_NULL;
+    if (!use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !out_aligned(out, p->out_dtype)) return TA_ERR_ALIGN;
     const ta_status s1 = ta_energy(p, q, K, workspace, workspace_bytes_given, lse, stream);
     if (s1 != TA_OK) return s1;
-    if (reinterpret_cast<uintptr_t>(out) & (p->out_dtype == TA_BF16 ? 1u : 3u)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     float *part_o = static_cast<float *>(workspace);
     const ta_status s2 = run_partial(p, q, K, V, P, nullptr, nullptr, nullptr, part_o, lse, 2, stream);

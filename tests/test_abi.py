@@ -117,6 +117,31 @@ def test_null_alignment_and_workspace_errors(lib):
     assert ta.ta_tree_combine(1, 32, 128, 4, FAKE, FAKE, FAKE, FAKE, 5, FAKE, None) == 3
 
 
+def test_energy_and_two_pass_argument_checks(lib):
+    p = llama_problem()
+    need = ta.ta_workspace_bytes(p, ta.ta_suggest_chunks(p))
+    assert ta.ta_energy(p, FAKE, FAKE, FAKE, need, None, None) == 1
+    assert ta.ta_energy(p, FAKE, FAKE, FAKE, need - 1, FAKE, None) == 5
+    assert ta.ta_energy(p, FAKE, FAKE + 4, FAKE, need, FAKE, None) == 4
+    assert ta.ta_decode_two_pass(p, FAKE, FAKE, None, FAKE, need, FAKE, FAKE, None) == 1
+    assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4   # checked before any launch
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4
+    p.qkv_dtype = ta.TA_F32      # the energy / two-pass routes exist on the bf16 d=128 kernel only
+    p.k_stride_n = p.v_stride_n = 128
+    assert ta.ta_energy(p, FAKE, FAKE, FAKE, 1 << 30, FAKE, None) == 6
+    assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
+
+
+def test_ragged_problems_reserve_workspace_for_the_balanced_launch(lib):
+    p = llama_problem()
+    p.B = 16
+    p.k_stride_b = p.v_stride_b = 8 * 131072 * 128
+    plain = ta.ta_workspace_bytes(p, 1)
+    p.valid_len = FAKE
+    # 256 shares + 16 x 8 segments, 4 rows of 130 floats each, plus the prefix table
+    assert ta.ta_workspace_bytes(p, 1) >= (256 + 128) * 4 * 130 * 4 + 17 * 8 > plain
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     from paper_2408_04093_amd import _ffi
     monkeypatch.setattr(_ffi, "_lib", None)
