@@ -643,6 +643,14 @@ def test_skewed_ragged_batch_is_balanced_over_the_device():
     check_multi(wm)
 
 
+def test_ragged_batch_with_no_keys_at_all():
+    w = W.make_qkv(3, 8, 2, 128, 500, torch.bfloat16, seed=85, device="cuda")
+    w.valid_len = torch.zeros(3, dtype=torch.int32, device="cuda")
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert not out.any().item() and torch.isneginf(lse).all().item()
+
+
 def test_very_large_ragged_batch_falls_back_to_chunks():
     """More sequences than the balanced launch tabulates (2048): fixed-size chunks instead."""
     B = 2100
