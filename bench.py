@@ -37,6 +37,9 @@ def build_workload(name, device, copy):
         if KEYS_OVERRIDE:
             return W.llama128k(N=KEYS_OVERRIDE, device=device, seed_offset=copy)
         return W.llama128k(device=device, seed_offset=copy)
+    if name == "d64_256k":
+        # head dimension 64 at the headline shape's byte count (the matrix-core kernel's 64-bit-load form)
+        return W.llama128k(N=262144, d=64, device=device, seed_offset=7 + copy)
     if name == "million":
         return W.million(device=device)
     if name == "ragged":
@@ -251,7 +254,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "d64_256k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
                     help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "

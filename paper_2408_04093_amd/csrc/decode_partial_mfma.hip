@@ -39,6 +39,7 @@ namespace ta {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -52,11 +53,26 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int D = 128;
 constexpr int kTile = 32;                       // keys per wave step
-constexpr int kPitch = 272;                     // LDS bytes per staged K row
-constexpr int kStage = kTile * kPitch;          // per wave
 constexpr int kMaxHeads = 16;
+
+// Head-dimension geometry.  A K or V row (2 D bytes) is always spread over 16 lanes, so a lane
+// holds D / 16 consecutive columns of each of its 8 keys: 128-bit loads at d = 128, 64-bit at d = 64.
+template <int D>
+struct Geo {
+    static_assert(D == 128 || D == 64, "head dimension");
+    static constexpr int kCols = D / 16;            // columns per lane = PV tiles of 16 columns
+    static constexpr int kLaneBytes = 2 * kCols;    // bytes per lane per row
+    static constexpr int kWords = kCols / 2;        // dwords per lane per row
+    static constexpr int kSteps = D / 32;           // k-steps of the QK^T contraction
+    static constexpr int kPitch = 2 * D + 16;       // LDS bytes per staged K row (16-byte pad: conflict-free A reads)
+    static constexpr int kStage = kTile * kPitch;   // per wave
+    typedef int row_t __attribute__((ext_vector_type(kWords)));   // one lane's share of one row
+    static __device__ __forceinline__ row_t load(__amdgpu_buffer_rsrc_t rs, int off) {
+        if constexpr (D == 128) return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, TA_AUX);
+        else return __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, TA_AUX);
+    }
+};
 
 // tile row owned by (row group r, slot e): e = 4G + i  ->  16G + 4r + i
 __device__ __forceinline__ int kappa(int r, int e) { return 16 * (e >> 2) + 4 * r + (e & 3); }
@@ -90,9 +106,13 @@ struct Range {
 
 // The whole streaming computation for one range: called once per workgroup by the chunked kernel
 // and once per piece by the balanced kernel.  smem / lds_m / lds_l are the workgroup's LDS areas.
-template <int MODE, int NRB, bool BALANCED>
+template <int D, int MODE, int NRB, bool BALANCED>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &rg, char *smem,
                                               float (*lds_m)[kMaxHeads], float (*lds_l)[kMaxHeads]) {
+    using G_ = Geo<D>;
+    using row_t = typename G_::row_t;
+    constexpr int kCols = G_::kCols, kSteps = G_::kSteps, kPitch = G_::kPitch, kStage = G_::kStage;
+    constexpr int kLaneBytes = G_::kLaneBytes;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -147,7 +167,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // (token t sees keys < L - Sq + 1 + t; chunk-relative, clamped to [0, n]) and its slice of
     // Q^T as MFMA B operand: lane (kb = r, row c) holds q[row][32t + 8r .. +8], zero for padding.
     int my_row[NRB], nlim[NRB];
-    bf16x8 qb[NRB][4];
+    bf16x8 qb[NRB][kSteps];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         const int row = 16 * rb + c;
@@ -156,7 +176,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         nlim[rb] = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
         const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row[rb])) * D + 8 * r) * 2;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kSteps; ++t) {
             v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
             if (row >= nrows) raw = v4i{0, 0, 0, 0};
             qb[rb][t] = __builtin_bit_cast(bf16x8, raw);
@@ -184,38 +204,38 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         trow[e] = kappa(r, e);
-        koff[e] = (uint32_t)(w * kTile + trow[e]) * a.k_row_bytes + c * 16;
-        voff[e] = (uint32_t)(w * kTile + trow[e]) * a.v_row_bytes + c * 16;
+        koff[e] = (uint32_t)(w * kTile + trow[e]) * a.k_row_bytes + c * kLaneBytes;
+        voff[e] = (uint32_t)(w * kTile + trow[e]) * a.v_row_bytes + c * kLaneBytes;
     }
     char *stage = smem + w * kStage;
 
-    auto issue_k = [&](v4i (&kr)[8], int it) {
+    auto issue_k = [&](row_t (&kr)[8], int it) {
         if (it < n_full) {
             const uint32_t inc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                kr[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[e] + inc), 0, TA_AUX);
+                kr[e] = G_::load(krs, (int)(koff[e] + inc));
         } else {   // ragged last steps: rows past the chunk are redirected to its last row
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 int row = it * ROWS_ITER + w * kTile + trow[e];
                 row = row < n ? row : n - 1;
-                kr[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)((uint32_t)row * a.k_row_bytes + c * 16), 0, TA_AUX);
+                kr[e] = G_::load(krs, (int)((uint32_t)row * a.k_row_bytes + c * kLaneBytes));
             }
         }
     };
-    auto issue_v = [&](v4i (&vr)[8], int it) {
+    auto issue_v = [&](row_t (&vr)[8], int it) {
         if (it < n_full) {
             const uint32_t inc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                vr[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[e] + inc), 0, TA_AUX);
+                vr[e] = G_::load(vrs, (int)(voff[e] + inc));
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 int row = it * ROWS_ITER + w * kTile + trow[e];
                 row = row < n ? row : n - 1;
-                vr[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)((uint32_t)row * a.v_row_bytes + c * 16), 0, TA_AUX);
+                vr[e] = G_::load(vrs, (int)((uint32_t)row * a.v_row_bytes + c * kLaneBytes));
             }
         }
     };
@@ -223,7 +243,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     const float cs = (float)a.c;   // scale * log2(e)
     float m_run[NRB];              // running max of this lane's row (log2 units), same in all 4 row groups
     float l_run[NRB];              // this lane's share of the row's normaliser
-    f32x4 acc[NRB][8];             // acc[rb][j][i] = O[row 16rb + 4r + i][col 8c + j]
+    f32x4 acc[NRB][kCols];         // acc[rb][j][i] = O[row 16rb + 4r + i][col kCols c + j]
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         m_run[rb] = -__builtin_huge_valf();
@@ -235,32 +255,32 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             m_run[rb] = given == -__builtin_huge_valf() ? __builtin_huge_valf() : given * (float)kLog2e;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < kCols; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     // One pipeline step on the register tiles (kr, vr) holding step `it`; the tiles are refilled
     // with step it + TA_DEPTH as soon as they have been consumed.
-    auto step = [&](v4i (&kr)[8], v4i (&vr)[8], int it) {
+    auto step = [&](row_t (&kr)[8], row_t (&vr)[8], int it) {
         const bool masked = it >= n_full;
         // ---- K tile: registers -> LDS (row-major, padded) -> A layout
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            *reinterpret_cast<v4i *>(stage + trow[e] * kPitch + c * 16) = kr[e];
+            *reinterpret_cast<row_t *>(stage + trow[e] * kPitch + c * kLaneBytes) = kr[e];
         if (it + TA_DEPTH < n_iters) issue_k(kr, it + TA_DEPTH);
 
         // S = K Q^T.  The 2 key groups x NRB row blocks are independent accumulation chains; the
         // k-step loop is outermost so that consecutive MFMAs never depend on each other.
-        v4i af[2][4];
+        v4i af[2][kSteps];
 #pragma unroll
         for (int G = 0; G < 2; ++G)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < kSteps; ++t)
                 af[G][t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
         f32x4 s[NRB][2];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) s[rb][0] = s[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < kSteps; ++t)
 #pragma unroll
             for (int G = 0; G < 2; ++G)
 #pragma unroll
@@ -311,7 +331,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                         for (int i = 0; i < 4; ++i) {
                             const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
 #pragma unroll
-                            for (int j = 0; j < 8; ++j) acc[rb][j][i] *= ai;
+                            for (int j = 0; j < kCols; ++j) acc[rb][j][i] *= ai;
                         }
                     }
                 }
@@ -342,10 +362,10 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
 
         if constexpr (MODE != kEnergy) {
-            // ---- PV: for each of this lane's 8 columns, interleave key pairs into B layout (once
+            // ---- PV: for each of this lane's columns, interleave key pairs into B layout (once
             // for all row blocks)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kCols; ++j) {
                 uint32_t bj[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -366,7 +386,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 
     // TA_DEPTH register tiles in rotation (1 measured as good as 2 or 3: the stream is DRAM-bound,
     // not latency-bound, and one tile keeps two workgroups resident per CU)
-    v4i kr[TA_DEPTH][8], vr[TA_DEPTH][8];
+    row_t kr[TA_DEPTH][8], vr[TA_DEPTH][8];
 #pragma unroll
     for (int x = 0; x < TA_DEPTH; ++x) {
         if (x < n_iters) {
@@ -397,7 +417,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 const int h = 4 * r + i;
                 if (h < brows) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) lds_o[(w * 16 + h) * D + 8 * c + j] = acc[rb][j][i];
+                    for (int j = 0; j < kCols; ++j) lds_o[(w * 16 + h) * D + kCols * c + j] = acc[rb][j][i];
                 }
             }
         }
@@ -471,15 +491,15 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 }
 
 // Chunked launch: one workgroup per (batch, kv head, token slice, chunk).
-template <int MODE, int NRB>
+template <int D, int MODE, int NRB>
 __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ float lds_m[kWaves][kMaxHeads];
     __shared__ float lds_l[kWaves][kMaxHeads];
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
-    process_range<MODE, NRB, false>(a, rg, smem, lds_m, lds_l);
+    process_range<D, MODE, NRB, false>(a, rg, smem, lds_m, lds_l);
 }
 
 // Balanced launch for ragged batches (lengths known only on the device).  The keys of all
@@ -494,16 +514,17 @@ __global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const Par
 // the time a CU streams ~200 keys), so a workgroup that gets a run of tiny sequences gets fewer of
 // them.  Without the charge a share made of ~100 tiny segments took 2x the time of the others.
 constexpr int kMaxBalancedB = 2048;   // sequences whose prefix sums fit the LDS table
-constexpr int kMinShare = 512;        // virtual keys: never cut finer than this
-constexpr int kPieceCost = 256;       // virtual keys charged per non-empty segment
+constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many bytes of K (512 keys at d = 128)
+constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
 
-template <int NRB>
+template <int D, int NRB>
 __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const PartialArgs a) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * kStage];
+    __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ float lds_m[kWaves][kMaxHeads];
     __shared__ float lds_l[kWaves][kMaxHeads];
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
     __shared__ int64_t sh_scan[kWaves];
+    constexpr int kMinShare = kMinShareBytes / (2 * D), kPieceCost = kPieceCostBytes / (2 * D);   // in keys
 
     const int tid = threadIdx.x;
     auto len_of = [&](int bb) -> int64_t {   // virtual length of one segment of sequence bb
@@ -581,7 +602,7 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
                            (int64_t)blockIdx.x + (int64_t)b * G + j};
             if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
             first = false;
-            process_range<kFull, NRB, true>(a, rg, smem, lds_m, lds_l);
+            process_range<D, kFull, NRB, true>(a, rg, smem, lds_m, lds_l);
         }
         x += span;
     }
@@ -589,41 +610,55 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
 
 }  // namespace
 
-template <int NRB>
+template <int D, int NRB>
 hipError_t launch_mode(const PartialArgs &a, int mode, dim3 grid, hipStream_t s) {
     switch (mode) {
-        case kEnergy: hipLaunchKernelGGL((decode_partial_mfma_kernel<kEnergy, NRB>), grid, dim3(kThreads), 0, s, a); break;
-        case kGradient: hipLaunchKernelGGL((decode_partial_mfma_kernel<kGradient, NRB>), grid, dim3(kThreads), 0, s, a); break;
-        default: hipLaunchKernelGGL((decode_partial_mfma_kernel<kFull, NRB>), grid, dim3(kThreads), 0, s, a); break;
+        case kEnergy: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kEnergy, NRB>), grid, dim3(kThreads), 0, s, a); break;
+        case kGradient: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kGradient, NRB>), grid, dim3(kThreads), 0, s, a); break;
+        default: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kFull, NRB>), grid, dim3(kThreads), 0, s, a); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s) {
+template <int D>
+hipError_t launch_rows(const PartialArgs &a, int mode, hipStream_t s) {
     const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
     const int rows = a.tq * a.g;
-    if (rows <= 16) return launch_mode<1>(a, mode, grid, s);
-    if (rows <= 32) return launch_mode<2>(a, mode, grid, s);
-    return launch_mode<4>(a, mode, grid, s);
+    if (rows <= 16) return launch_mode<D, 1>(a, mode, grid, s);
+    if (rows <= 32) return launch_mode<D, 2>(a, mode, grid, s);
+    return launch_mode<D, 4>(a, mode, grid, s);
 }
 
-hipError_t launch_decode_balanced_mfma(const PartialArgs &a, hipStream_t s) {
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hipStream_t s) {
+    if (d == 128) return launch_rows<128>(a, mode, s);
+    if (d == 64) return launch_rows<64>(a, mode, s);
+    return hipErrorInvalidValue;
+}
+
+template <int D>
+hipError_t launch_balanced(const PartialArgs &a, hipStream_t s) {
     const dim3 grid((uint32_t)a.W);
     const int rows = a.tq * a.g;
-    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<1>), grid, dim3(kThreads), 0, s, a);
-    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<2>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<4>), grid, dim3(kThreads), 0, s, a);
+    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
+    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 2>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
+hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, hipStream_t s) {
+    if (d == 128) return launch_balanced<128>(a, s);
+    if (d == 64) return launch_balanced<64>(a, s);
+    return hipErrorInvalidValue;
+}
+
 int balanced_max_batch() { return kMaxBalancedB; }
-int balanced_min_share() { return kMinShare; }
-int balanced_piece_cost() { return kPieceCost; }
+int balanced_min_share(int d) { return kMinShareBytes / (2 * d); }
+int balanced_piece_cost(int d) { return kPieceCostBytes / (2 * d); }
 
 int decode_partial_mfma_occupancy() {
     static const int cached = [] {
         int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<kFull, 1>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<128, kFull, 1>, kThreads, 0) !=
                 hipSuccess || nb < 1) {
             (void)hipGetLastError();
             nb = 2;

@@ -92,7 +92,9 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     const int64_t groups = launch_groups(p);
     int64_t P;
     if (use_mfma_path(p->qkv_dtype, p->d)) {
-        constexpr int64_t kLongChunk = 32768, kRaggedChunk = 4096, kBalancedChunk = 2048;
+        // thresholds tuned at d = 128 in keys; what matters is bytes, so d = 64 doubles them
+        const int64_t kd = 128 / p->d;
+        const int64_t kLongChunk = 32768 * kd, kRaggedChunk = 4096 * kd, kBalancedChunk = 2048 * kd;
         const int64_t per_round = cus / groups;
         if (p->valid_len) {
             P = (p->N + kRaggedChunk - 1) / kRaggedChunk;
@@ -216,7 +218,7 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     a.t = (p->N + P - 1) / P;
     if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
     const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
-                             ? launch_decode_partial_mfma(a, mode, static_cast<hipStream_t>(stream))
+                             ? launch_decode_partial_mfma(a, p->d, mode, static_cast<hipStream_t>(stream))
                              : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
@@ -297,14 +299,14 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
         a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
         a.W = bp.W;
         a.piece_rows = bp.rows;
-        if (launch_decode_balanced_mfma(a, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
+        if (launch_decode_balanced_mfma(a, p->d, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
         CombineArgs c{};
         c.part_m = a.part_m; c.part_l = a.part_l; c.part_o = a.part_o;
         c.out = out; c.lse = lse;
         c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = 0;
         c.out_dtype = p->out_dtype;
         c.cum = a.cum;
-        c.W = bp.W; c.min_share = balanced_min_share(); c.piece_cost = balanced_piece_cost(); c.piece_rows = bp.rows;
+        c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
         c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.tq = a.tq;
         return launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
     }

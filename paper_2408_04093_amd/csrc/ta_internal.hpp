@@ -54,9 +54,9 @@ struct CombineArgs {
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s);
 hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s);
 
-// bf16 with d = 128 runs on the matrix-core kernel (any group size up to 16 in
-// one pass); everything else on the VALU kernel.
-inline bool use_mfma_path(int dtype, int d) { return dtype == TA_BF16 && d == 128; }
+// bf16 runs on the matrix-core kernel (any group size up to 16 in one pass);
+// fp32 on the VALU kernel.
+inline bool use_mfma_path(int dtype, int d) { return dtype == TA_BF16 && (d == 128 || d == 64); }
 
 // Heads of one GQA group handled by one workgroup for a given group size.
 inline int heads_per_workgroup(int dtype, int d, int g) {
@@ -68,13 +68,13 @@ inline int heads_per_workgroup(int dtype, int d, int g) {
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
 // resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
 int decode_partial_occupancy(int dtype, int d, int gt);
-// bf16, d = 128.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)
-hipError_t launch_decode_partial_mfma(const PartialArgs &a, int mode, hipStream_t s);
+// bf16, d in {64, 128}.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)
+hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hipStream_t s);
 int decode_partial_mfma_occupancy();
-hipError_t launch_decode_balanced_mfma(const PartialArgs &a, hipStream_t s);
+hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, hipStream_t s);
 int balanced_max_batch();
-int balanced_min_share();
-int balanced_piece_cost();
+int balanced_min_share(int d);     // virtual keys
+int balanced_piece_cost(int d);    // virtual keys
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 
 }  // namespace ta

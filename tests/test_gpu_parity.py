@@ -12,8 +12,9 @@ implementation can promise 2e-3 per row.  Both sides therefore take the
 rounding decision in the same way: the GPU's bf16 output must equal
 round-to-nearest-even of its own fp32 output bit for bit, must be within one
 bf16 ulp of round-to-nearest-even of the oracle everywhere (or within 1e-4 of
-the row's rms for elements far below the row's scale), differing on at most
-0.5% of elements (where the fp32 value sits on a rounding boundary), and
+the row's rms for elements far below the row's scale), may differ from it only
+where the oracle's value lies within the fp32 path's own error (4 x 5e-5 of
+the row's rms per element) of the rounding boundary between the two codes, and
 its rel-L2 over the whole tensor must be <= 2e-3 once the tensor is large
 enough (>= 2048 elements) for that statistic to be stable.
 """
@@ -82,7 +83,9 @@ def check_bf16_output(out_b, out_f32, ref_out):
     rms = np.sqrt((ref_out ** 2).mean(axis=-1, keepdims=True))
     small = np.abs(out_b - ref_b) <= 1e-4 * rms
     assert ((ulp <= 1) | small).all()
-    assert (ulp != 0).sum() <= 1 + 0.005 * ulp.size
+    # a different code is legitimate only where the exact value sits on a rounding boundary
+    boundary = 0.5 * (out_b.astype(np.float64) + ref_b)
+    assert ((ulp == 0) | small | (np.abs(ref_out - boundary) <= 4 * TOL_BF16_F32OUT * rms)).all()
     if ref_out.size >= 2048:
         assert np.linalg.norm(out_b - ref_out) / np.linalg.norm(ref_out) <= TOL_BF16
 
@@ -142,6 +145,7 @@ SHAPES = [
     ("bf16", 1, 8, 1, 128, 777), ("bf16", 1, 2, 1, 128, 4099), ("bf16", 1, 1, 1, 128, 300),
     ("bf16", 1, 3, 1, 128, 513), ("bf16", 1, 16, 1, 128, 600), ("bf16", 2, 12, 2, 128, 257),
     ("bf16", 1, 4, 1, 64, 1031), ("bf16", 1, 8, 1, 64, 129), ("bf16", 1, 1, 1, 64, 5),
+    ("bf16", 1, 16, 1, 64, 4099), ("bf16", 2, 12, 2, 64, 257), ("bf16", 2, 3, 1, 64, 1), ("bf16", 1, 2, 2, 64, 777),
     ("f32", 1, 1, 1, 64, 1025), ("f32", 2, 4, 2, 64, 300), ("f32", 1, 8, 1, 64, 200),
     ("f32", 1, 2, 1, 128, 519), ("f32", 1, 4, 1, 128, 64), ("f32", 1, 1, 1, 128, 7),
 ]
@@ -318,7 +322,7 @@ def test_long_chunk_table_beyond_the_ranked_limit():
 
 
 @pytest.mark.parametrize("dt,d", [("bf16", 64), ("f32", 64), ("f32", 128)])
-def test_ragged_lengths_on_the_valu_kernels(dt, d):
+def test_ragged_lengths_d64_and_fp32(dt, d):
     dtype = torch.bfloat16 if dt == "bf16" else torch.float32
     w = W.make_qkv(4, 8, 2, d, 900, dtype, seed=17, device="cuda")
     w.valid_len = torch.tensor([900, 0, 257, 31], dtype=torch.int32, device="cuda")
@@ -436,13 +440,16 @@ def check_multi(w):
     return ref_out, ref_lse
 
 
-@pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [
+@pytest.mark.parametrize("B,Sq,Hq,Hkv,N,d", [c if len(c) == 6 else c + (128,) for c in [
     (1, 2, 4, 1, 300), (2, 4, 8, 2, 1000), (1, 16, 1, 1, 777), (1, 3, 8, 1, 513),
     (1, 8, 32, 8, 4099), (2, 5, 16, 16, 129), (1, 7, 12, 2, 2048), (1, 4, 16, 1, 640),
     # 17..64 (token, head) rows: two and four row blocks in one pass; beyond 64: token slices
-    (1, 16, 32, 8, 1500), (1, 5, 8, 1, 900), (2, 20, 4, 1, 700), (1, 5, 16, 1, 333), (1, 40, 2, 2, 400)])
-def test_multi_token_causal_decode(B, Sq, Hq, Hkv, N):
-    w = W.make_multi(B, Sq, Hq, Hkv, 128, N, torch.bfloat16, seed=77 + Sq + N, device="cuda")
+    (1, 16, 32, 8, 1500), (1, 5, 8, 1, 900), (2, 20, 4, 1, 700), (1, 5, 16, 1, 333), (1, 40, 2, 2, 400),
+    # d = 64: one, two and four row blocks, and token slices
+    (2, 4, 8, 2, 1000, 64), (1, 3, 8, 1, 513, 64), (1, 16, 32, 8, 1500, 64), (1, 5, 16, 1, 333, 64),
+    (2, 20, 4, 1, 700, 64), (1, 7, 12, 2, 2048, 64)]])
+def test_multi_token_causal_decode(B, Sq, Hq, Hkv, N, d):
+    w = W.make_multi(B, Sq, Hq, Hkv, d, N, torch.bfloat16, seed=77 + Sq + N, device="cuda")
     check_multi(w)
     if B > 1:
         w.valid_len = torch.tensor([N, max(1, N // 3)][:B], dtype=torch.int32, device="cuda")
@@ -467,8 +474,8 @@ def test_multi_token_more_tokens_than_keys_and_chunks_inside_the_new_tokens():
     assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
 
 
-def test_multi_token_needs_bf16_d128():
-    w = W.make_multi(1, 2, 4, 1, 64, 100, torch.bfloat16, seed=1, device="cuda")
+def test_multi_token_needs_bf16():
+    w = W.make_multi(1, 2, 4, 1, 64, 100, torch.float32, seed=1, device="cuda")
     with pytest.raises(ta.TAError) as e:
         ta.decode(w.q, w.K, w.V, w.scale)
     assert e.value.code == 6
@@ -523,15 +530,16 @@ def test_graph_capture_and_replay():
 
 
 # ------------------------------------------------------------------ energy pass and the two-pass route (Algorithms 1 and 2)
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [(1, 1, 4, 1, 1), (2, 1, 8, 2, 1000), (1, 1, 16, 1, 4099),
                                             (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000), (1, 12, 8, 2, 600),
                                             (1, 9, 16, 2, 450)])
-def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N):
+def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N, d):
     if Sq == 1:
-        w = W.make_qkv(B, Hq, Hkv, 128, N, torch.bfloat16, seed=300 + N, device="cuda")
+        w = W.make_qkv(B, Hq, Hkv, d, N, torch.bfloat16, seed=300 + N, device="cuda")
         ref_fn = oracle.decode
     else:
-        w = W.make_multi(B, Sq, Hq, Hkv, 128, N, torch.bfloat16, seed=300 + N, device="cuda")
+        w = W.make_multi(B, Sq, Hq, Hkv, d, N, torch.bfloat16, seed=300 + N, device="cuda")
         ref_fn = oracle.decode_causal
     if B > 1:
         w.valid_len = torch.tensor([N, N // 2][:B], dtype=torch.int32, device="cuda")
@@ -568,6 +576,13 @@ def test_energy_of_an_empty_sequence_and_unsupported_types():
     assert e.value.code == 6
 
 
+def test_d64_heads_256k_full():
+    """Head dimension 64 at the headline shape's byte count: 32 heads over 8 kv heads, 256k keys."""
+    w = W.llama128k(N=262144, d=64, device="cuda", seed_offset=7)
+    assert w.shape == (1, 32, 8, 64, 262144)
+    check(w)
+
+
 def test_energy_llama_128k_full():
     w = W.llama128k(device="cuda")
     ref_out, ref_lse = oracle_of(w)
@@ -578,10 +593,11 @@ def test_energy_llama_128k_full():
     assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
 
 
-def test_batched_short_contexts_take_the_single_chunk_path():
+@pytest.mark.parametrize("d", [128, 64])
+def test_batched_short_contexts_take_the_single_chunk_path(d):
     """64 sequences x 4 kv heads = one workgroup per CU with P = 1: out and lse come straight from
     the streaming kernel (no partials, no combine launch)."""
-    w = W.make_qkv(64, 8, 4, 128, 3000, torch.bfloat16, seed=71, device="cuda")
+    w = W.make_qkv(64, 8, 4, d, 3000, torch.bfloat16, seed=71, device="cuda")
     p = ta.make_problem(w.q, w.K, w.V, w.scale)
     assert ta.ta_suggest_chunks(p) == 1
     check(w)
@@ -595,7 +611,7 @@ def test_batched_short_contexts_take_the_single_chunk_path():
     lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
     torch.cuda.synchronize()
     assert lse_err(lse_e.cpu().numpy(), lse.astype(np.float64)) <= 1e-5
-    wm = W.make_multi(64, 3, 8, 4, 128, 500, torch.bfloat16, seed=72, device="cuda")
+    wm = W.make_multi(64, 3, 8, 4, d, 500, torch.bfloat16, seed=72, device="cuda")
     assert ta.ta_suggest_chunks(ta.make_problem(wm.q, wm.K, wm.V, wm.scale)) == 1
     check_multi(wm)
 
@@ -620,11 +636,12 @@ def test_largest_supported_head_slice():
     assert not torch.equal(lse, lse2)
 
 
-def test_skewed_ragged_batch_is_balanced_over_the_device():
+@pytest.mark.parametrize("d", [128, 64])
+def test_skewed_ragged_batch_is_balanced_over_the_device(d):
     """One long sequence among many short and empty ones: the balanced launch cuts all keys into
     equal shares, so pieces cross sequence and head boundaries in every combination."""
     B, N = 24, 40000
-    w = W.make_qkv(B, 8, 2, 128, N, torch.bfloat16, seed=81, device="cuda")
+    w = W.make_qkv(B, 8, 2, d, N, torch.bfloat16, seed=81, device="cuda")
     g = torch.Generator().manual_seed(8)
     vl = torch.randint(1, 300, (B,), generator=g, dtype=torch.int32)
     vl[3] = N; vl[0] = 0; vl[7] = 0; vl[23] = 0; vl[11] = 1; vl[12] = 2
@@ -635,10 +652,10 @@ def test_skewed_ragged_batch_is_balanced_over_the_device():
     out, lse = check(w)
     assert not out[0].any() and np.isneginf(lse[[0, 7, 23]]).all()
     # several query tokens through the same path (token slices become extra segments)
-    wm = W.make_multi(6, 5, 16, 2, 128, 9000, torch.bfloat16, seed=82, device="cuda")   # 5 x 8 = 40 rows
+    wm = W.make_multi(6, 5, 16, 2, d, 9000, torch.bfloat16, seed=82, device="cuda")   # 5 x 8 = 40 rows
     wm.valid_len = torch.tensor([9000, 3, 0, 700, 5, 4321], dtype=torch.int32, device="cuda")
     check_multi(wm)
-    wm = W.make_multi(3, 9, 16, 1, 128, 2000, torch.bfloat16, seed=83, device="cuda")   # g = 16: 4 + 4 + 1 tokens
+    wm = W.make_multi(3, 9, 16, 1, d, 2000, torch.bfloat16, seed=83, device="cuda")   # g = 16: 4 + 4 + 1 tokens
     wm.valid_len = torch.tensor([2000, 8, 1234], dtype=torch.int32, device="cuda")
     check_multi(wm)
 
