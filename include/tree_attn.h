@@ -45,7 +45,7 @@
  *     ta_tree_combine pass Sq*Hq as Hq.  All tokens and heads of a KV group
  *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 64; beyond that the
  *     tokens are processed in slices of floor(64 / (Hq/Hkv)), each slice
- *     reading K/V once.  Sq > 1 needs bf16 inputs and d = 128.
+ *     reading K/V once.  Sq > 1 needs bf16 inputs.
  */
 #ifndef TREE_ATTN_H
 #define TREE_ATTN_H
@@ -154,7 +154,7 @@ ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
  * chunks into `workspace`, then ta_tree_combine.  When P = 1 (short contexts
  * in a large batch) the single chunk is the result: the streaming kernel
  * normalises and stores out / lse itself and no second kernel is launched.
- * When valid_len is given (a ragged batch; bf16, d = 128, B <= 2048) the chunks
+ * When valid_len is given (a ragged batch; bf16, B <= 2048) the chunks
  * are not fixed-size: all valid keys of the batch are cut into one equal-cost
  * share per compute unit on the device, whatever the mix of lengths, and the
  * combine merges each row's pieces.  The result is the same attention output;
@@ -175,7 +175,7 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
  * an argument and only K is streamed: half the bytes of ta_decode.
  *   workspace   as for ta_decode (same size and alignment)
  *   lse         fp32 [B,Hq] ([B,Sq,Hq])
- * bf16, d = 128 only (TA_ERR_UNSUPPORTED otherwise).
+ * bf16 only (TA_ERR_UNSUPPORTED otherwise).
  */
 ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
                     void *workspace, size_t workspace_bytes, float *lse, void *stream);
@@ -187,7 +187,7 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
  * With lse known no running max and no normaliser are needed and the chunk
  * partials add up plainly.  K is streamed twice (1.5 x the bytes of ta_decode);
  * it exists as an on-GPU cross-check of Observation 1 and for callers that
- * already hold lse.  Arguments as for ta_decode.  bf16, d = 128 only.
+ * already hold lse.  Arguments as for ta_decode.  bf16 only.
  */
 ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
                              void *workspace, size_t workspace_bytes,

@@ -1,17 +1,17 @@
 // decode_partial, vector-ALU form: per-chunk partial softmax statistics
 // (m, l, o) for one query token, all heads of a GQA group at once.  This kernel
-// serves fp32 K/V and d = 64; bf16 with d = 128 runs on the matrix-core kernel
-// in decode_partial_mfma.hip.  Tree Attention (arXiv 2408.04093)
+// serves fp32 K/V; bf16 runs on the matrix-core kernel in
+// decode_partial_mfma.hip.  Tree Attention (arXiv 2408.04093)
 // Algorithm 3 steps 1-2 with the chunks mapped to workgroups of one gfx950 GPU
 // instead of devices; inside a chunk it is the running-max form of the
 // Section 3 recurrence (n_i = n_{i-1} + v_i s_i, d_i = d_{i-1} + s_i) made safe
 // by the max shift of Appendix F.
 //
 // Data movement (the whole cost: the kernel is HBM-bound)
-//   * A K or V row is D elements = 128..512 bytes.  LPR = row_bytes/16 lanes
+//   * A K or V row is D fp32 = 256 or 512 bytes.  LPR = row_bytes/16 lanes
 //     each fetch 16 bytes of it with one 128-bit buffer load, so a wave-wide
 //     load covers RPW = 64/LPR complete rows, fully coalesced.
-//   * Every lane therefore owns EPL = 8 (bf16) or 4 (fp32) fixed columns of
+//   * Every lane therefore owns EPL = 4 fixed columns of
 //     the head dimension and one of RPW interleaved "row groups" of keys.
 //     Each row group runs its own online softmax; they are merged at the end.
 //   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
@@ -21,9 +21,8 @@
 //     registers: every K/V byte is fetched once per group.
 //
 // Arithmetic
-//   bf16: q.k with v_dot2_f32_bf16 (fp32 accumulate), everything else fp32.
-//   fp32: q.k and the running max in fp64 (full rate on gfx950) so that large
-//         |score| does not cost precision; exponentials and sums in fp32.
+//   q.k and the running max in fp64 (full rate on gfx950) so that large
+//   |score| does not cost precision; exponentials and sums in fp32.
 //   Scores are kept in log2 units (score * scale * log2 e) so the exponential
 //   is the bare v_exp_f32; the partial is converted to natural units on store.
 #include "chunking.hpp"
@@ -34,7 +33,6 @@ namespace ta {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Tuning constants (overridable at compile time for sweeps)
 #ifndef TA_U
@@ -52,59 +50,21 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int kThreads = TA_THREADS;
 constexpr int kWaves = kThreads / kWave;
 
-template <int DT> struct Elem;
-template <> struct Elem<TA_BF16> {
-    static constexpr int kBytes = 2;
-    using acc_t = float;    // score / running-max type
-    using q_t = uint32_t;   // one register = two bf16 of q
-};
-template <> struct Elem<TA_F32> {
-    static constexpr int kBytes = 4;
-    using acc_t = double;
-    using q_t = double;     // q widened once
-};
+constexpr int kBytes = 4;   // fp32 K/V
+constexpr int EPL = 4;      // columns per lane: one 128-bit load
+using acc_t = double;       // score / running-max type
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
     // raw buffer (stride 0): hardware returns 0 for any access past `bytes`
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-// Reinterpret one 32-bit register as two bf16.  Takes the value, not a vector
-// subscript: bit-casting `vec[i]` directly loses the index in this compiler.
-__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t x) {
-    bf16x2 r;
-    __builtin_memcpy(&r, &x, sizeof r);
-    return r;
-}
-
-// partial dot product of this lane's 16 bytes of a key row with q
-__device__ __forceinline__ float lane_dot(const v4i &k, const uint32_t (&q)[4]) {
-    const uint32_t k0 = (uint32_t)k.x, k1 = (uint32_t)k.y, k2 = (uint32_t)k.z, k3 = (uint32_t)k.w;
-    float acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k0), as_bf16x2(q[0]), 0.f, false);
-    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k1), as_bf16x2(q[1]), acc, false);
-    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k2), as_bf16x2(q[2]), acc, false);
-    acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(k3), as_bf16x2(q[3]), acc, false);
-    return acc;
-}
+// partial dot product of this lane's 16 bytes of a key row with q (q widened once to fp64)
 __device__ __forceinline__ double lane_dot(const v4i &k, const double (&q)[4]) {
     double acc = 0.0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc = fma((double)__int_as_float(k[r]), q[r], acc);
     return acc;
-}
-
-template <int DT, int EPL>
-__device__ __forceinline__ void widen_row(const v4i &v, float (&f)[EPL]) {
-    if constexpr (DT == TA_BF16) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            f[2 * r] = __uint_as_float((uint32_t)v[r] << 16);
-            f[2 * r + 1] = __uint_as_float((uint32_t)v[r] & 0xffff0000u);
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) f[r] = __int_as_float(v[r]);
-    }
 }
 
 template <int U>
@@ -113,26 +73,22 @@ struct Tile {
     v4i v[U];
 };
 
-template <typename acc_t, int GT, int EPL>
+template <int GT>
 struct State {
     acc_t m[GT];        // running max, log2 units
     float l[GT];        // running normaliser
     float o[GT][EPL];   // running numerator, this lane's columns
 };
 
-template <typename acc_t> __device__ __forceinline__ acc_t neg_inf();
-template <> __device__ __forceinline__ float neg_inf<float>() { return -__builtin_huge_valf(); }
-template <> __device__ __forceinline__ double neg_inf<double>() { return -__builtin_huge_val(); }
+__device__ __forceinline__ acc_t neg_inf() { return -__builtin_huge_val(); }
 
 // One pipeline step: U keys per row group, GT heads.
 //   row0: chunk-relative index of this lane's first key (u = 0); key u is
 //   row0 + u*RPW.  MASKED steps treat rows >= n as absent.
-template <int DT, int D, int GT, int U, bool MASKED>
-__device__ __forceinline__ void step(const Tile<U> &T, const typename Elem<DT>::q_t (&q)[GT][4],
-                                     State<typename Elem<DT>::acc_t, GT, 16 / Elem<DT>::kBytes> &st,
-                                     typename Elem<DT>::acc_t c, int row0, int n) {
-    using acc_t = typename Elem<DT>::acc_t;
-    constexpr int EPL = 16 / Elem<DT>::kBytes, LPR = D / EPL, RPW = kWave / LPR;
+template <int D, int GT, int U, bool MASKED>
+__device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4], State<GT> &st, acc_t c, int row0,
+                                     int n) {
+    constexpr int LPR = D / EPL, RPW = kWave / LPR;
 
     acc_t s2[U][GT];
 #pragma unroll
@@ -142,7 +98,7 @@ __device__ __forceinline__ void step(const Tile<U> &T, const typename Elem<DT>::
             acc_t acc = group_sum<LPR>(lane_dot(T.k[u], q[h]));
             s2[u][h] = acc * c;
             if constexpr (MASKED)
-                if (row0 + u * RPW >= n) s2[u][h] = neg_inf<acc_t>();
+                if (row0 + u * RPW >= n) s2[u][h] = neg_inf();
         }
     }
 
@@ -172,7 +128,8 @@ __device__ __forceinline__ void step(const Tile<U> &T, const typename Elem<DT>::
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float vf[EPL];
-        widen_row<DT, EPL>(T.v[u], vf);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) vf[e] = __int_as_float(T.v[u][e]);
 #pragma unroll
         for (int h = 0; h < GT; ++h) {
             float p = exp2_hw((float)(s2[u][h] - st.m[h]));
@@ -185,12 +142,9 @@ __device__ __forceinline__ void step(const Tile<U> &T, const typename Elem<DT>::
     }
 }
 
-template <int DT, int D, int GT, int U>
+template <int D, int GT, int U>
 __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
-    using E = Elem<DT>;
-    using acc_t = typename E::acc_t;
-    using q_t = typename E::q_t;
-    constexpr int EPL = 16 / E::kBytes, LPR = D / EPL, RPW = kWave / LPR;
+    constexpr int LPR = D / EPL, RPW = kWave / LPR;
     constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
 
     const int tid = threadIdx.x;
@@ -217,24 +171,21 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     }
 
     // q: this lane's EPL columns of each head, kept in registers
-    q_t q[GT][4];
+    double q[GT][4];
 #pragma unroll
     for (int h = 0; h < GT; ++h) {
-        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + sub * EPL) * E::kBytes;
+        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + sub * EPL) * kBytes;
         const v4i raw = *reinterpret_cast<const v4i *>(qp);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if constexpr (DT == TA_BF16) q[h][r] = (uint32_t)raw[r];
-            else q[h][r] = (double)__int_as_float(raw[r]);
-        }
+        for (int r = 0; r < 4; ++r) q[h][r] = (double)__int_as_float(raw[r]);
     }
 
-    const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * E::kBytes +
+    const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * kBytes +
                      lo * (int64_t)a.k_row_bytes;
-    const char *vb = (const char *)a.V + ((int64_t)b * a.v_sb + (int64_t)hk * a.v_sh) * E::kBytes +
+    const char *vb = (const char *)a.V + ((int64_t)b * a.v_sb + (int64_t)hk * a.v_sh) * kBytes +
                      lo * (int64_t)a.v_row_bytes;
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kb, (uint32_t)(n - 1) * a.k_row_bytes + D * E::kBytes);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vb, (uint32_t)(n - 1) * a.v_row_bytes + D * E::kBytes);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kb, (uint32_t)(n - 1) * a.k_row_bytes + D * kBytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vb, (uint32_t)(n - 1) * a.v_row_bytes + D * kBytes);
 
     const int n_iters = (n + ROWS_ITER - 1) / ROWS_ITER;
     const int n_full = n / ROWS_ITER;
@@ -275,10 +226,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         }
     };
 
-    State<acc_t, GT, EPL> st;
+    State<GT> st;
 #pragma unroll
     for (int h = 0; h < GT; ++h) {
-        st.m[h] = neg_inf<acc_t>();
+        st.m[h] = neg_inf();
         st.l[h] = 0.f;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) st.o[h][e] = 0.f;
@@ -287,8 +238,8 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
     auto compute = [&](const Tile<U> &T, int it) {
         const int row0 = it * ROWS_ITER + row_lane;
-        if (it < n_full) step<DT, D, GT, U, false>(T, q, st, c, row0, n);
-        else step<DT, D, GT, U, true>(T, q, st, c, row0, n);
+        if (it < n_full) step<D, GT, U, false>(T, q, st, c, row0, n);
+        else step<D, GT, U, true>(T, q, st, c, row0, n);
     };
 
     // two register tiles, ping-pong: the loads of step it+1 are in flight
@@ -361,20 +312,20 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     }
 }
 
-template <int DT, int D, int GT>
+template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
     constexpr int U = TA_U;
     const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
-    hipLaunchKernelGGL((decode_partial_kernel<DT, D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
+    hipLaunchKernelGGL((decode_partial_kernel<D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
 // resident workgroups per compute unit of one instantiation (register-bound)
-template <int DT, int D, int GT>
+template <int D, int GT>
 int occupancy_one() {
     static const int cached = [] {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<DT, D, GT, TA_U>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, TA_U>, kThreads, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
@@ -386,34 +337,26 @@ int occupancy_one() {
 
 #define TA_DISPATCH(FN, ...)                                                                   \
     do {                                                                                       \
-        if (dtype == TA_BF16) {                                                                \
-            if (d == 128) { switch (gt) { case 8: return FN<TA_BF16, 128, 8>(__VA_ARGS__);     \
-                                          case 4: return FN<TA_BF16, 128, 4>(__VA_ARGS__);     \
-                                          case 2: return FN<TA_BF16, 128, 2>(__VA_ARGS__);     \
-                                          default: return FN<TA_BF16, 128, 1>(__VA_ARGS__); } } \
-            switch (gt) { case 8: return FN<TA_BF16, 64, 8>(__VA_ARGS__);                      \
-                          case 4: return FN<TA_BF16, 64, 4>(__VA_ARGS__);                      \
-                          case 2: return FN<TA_BF16, 64, 2>(__VA_ARGS__);                      \
-                          default: return FN<TA_BF16, 64, 1>(__VA_ARGS__); }                   \
-        }                                                                                      \
-        if (d == 128) { switch (gt) { case 8: return FN<TA_F32, 128, 8>(__VA_ARGS__);          \
-                                      case 4: return FN<TA_F32, 128, 4>(__VA_ARGS__);          \
-                                      case 2: return FN<TA_F32, 128, 2>(__VA_ARGS__);          \
-                                      default: return FN<TA_F32, 128, 1>(__VA_ARGS__); } }     \
-        switch (gt) { case 8: return FN<TA_F32, 64, 8>(__VA_ARGS__);                           \
-                      case 4: return FN<TA_F32, 64, 4>(__VA_ARGS__);                           \
-                      case 2: return FN<TA_F32, 64, 2>(__VA_ARGS__);                           \
-                      default: return FN<TA_F32, 64, 1>(__VA_ARGS__); }                        \
+        if (d == 128) { switch (gt) { case 8: return FN<128, 8>(__VA_ARGS__);                  \
+                                      case 4: return FN<128, 4>(__VA_ARGS__);                  \
+                                      case 2: return FN<128, 2>(__VA_ARGS__);                  \
+                                      default: return FN<128, 1>(__VA_ARGS__); } }             \
+        switch (gt) { case 8: return FN<64, 8>(__VA_ARGS__);                                   \
+                      case 4: return FN<64, 4>(__VA_ARGS__);                                   \
+                      case 2: return FN<64, 2>(__VA_ARGS__);                                   \
+                      default: return FN<64, 1>(__VA_ARGS__); }                                \
     } while (0)
 
 }  // namespace
 
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s) {
+    if (dtype != TA_F32) return hipErrorInvalidValue;   // bf16 belongs to the matrix-core kernel
     const int gt = a.g / a.slices;
     TA_DISPATCH(launch_one, a, s);
 }
 
 int decode_partial_occupancy(int dtype, int d, int gt) {
+    (void)dtype;
     TA_DISPATCH(occupancy_one);
 }
 

@@ -1,5 +1,6 @@
-// decode_partial on the matrix cores: bf16 K/V, d = 128, up to 16 query heads
-// per KV head in one pass.  Same contract as the VALU kernel in
+// decode_partial on the matrix cores: bf16 K/V, d = 128 or 64, up to 16 query
+// heads per KV head in one pass (the layout notes below are written for d = 128;
+// Geo<D> holds what changes at d = 64: 64-bit row loads, 2 k-steps, 4 PV tiles).  Same contract as the VALU kernel in
 // decode_partial.hip (Tree Attention, arXiv 2408.04093, Algorithm 3 steps 1-2:
 // per-chunk partial (m, l, o); Section 3 recurrence with the Appendix F max
 // shift), different arithmetic engine.

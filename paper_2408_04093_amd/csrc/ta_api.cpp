@@ -73,7 +73,7 @@ int device_compute_units() {
 
 // Chunk count (host-only heuristic, tuned on MI355X measurements).
 //
-// Matrix-core kernel (bf16, d = 128): with equal work per workgroup the best
+// Matrix-core kernel (bf16; figures for d = 128): with equal work per workgroup the best
 // launch is ONE workgroup per compute unit, each streaming one long contiguous
 // share (7.2 TB/s at 1M keys; two per CU or a ragged last round measured
 // 4-8 % slower).  So P = CUs / groups, times a whole number of rounds only
@@ -83,7 +83,7 @@ int device_compute_units() {
 // or chunks of kRaggedChunk keys: 4096 measured best on the ragged config, in
 // chunk-major launch order) for the hardware dispatcher to balance it.
 //
-// VALU kernel (fp32 or d = 64): rounds of CUs x resident workgroups, chunks
+// VALU kernel (fp32): rounds of CUs x resident workgroups, chunks
 // near 4096 keys.
 int32_t suggest_chunks(const ta_problem *p, int cus) {
     constexpr int64_t kMinChunk = 256;
