@@ -22,8 +22,9 @@
  *     (Section 3); the paper has no scale.
  *   - Grouped queries: g = Hq / Hkv, query head h reads KV head h / g (integer
  *     division).  The paper treats heads as independent (Appendix C.1); the
- *     grouping only changes which K/V a head reads.  All g heads of a group
- *     are processed by the same workgroup so that K/V bytes are fetched once.
+ *     grouping only changes which K/V a head reads.  With bf16 inputs up to 64
+ *     heads of a group are processed by the same workgroup so that K/V bytes
+ *     are fetched once per group (fp32 inputs: up to 8 heads per pass).
  *   - Keys at positions >= valid_len[b] do not exist and are never read.
  *   - lse is the natural-log logsumexp of the scaled scores over the valid
  *     keys, i.e. the energy F(0) of Observation 1; out is dF/dzeta at 0.
@@ -44,8 +45,8 @@
  *     lse [B,Sq,Hq], partials [B,Sq,Hq,P] and [B,Sq,Hq,P,d]; for
  *     ta_tree_combine pass Sq*Hq as Hq.  All tokens and heads of a KV group
  *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 64; beyond that the
- *     tokens are processed in slices of floor(64 / (Hq/Hkv)), each slice
- *     reading K/V once.  Sq > 1 needs bf16 inputs.
+ *     (token, head) pairs of the group, taken token-major, are processed in
+ *     slices of 64, each slice reading K/V once.  Sq > 1 needs bf16 inputs.
  */
 #ifndef TREE_ATTN_H
 #define TREE_ATTN_H
@@ -77,7 +78,7 @@ typedef enum { TA_BF16 = 0, TA_F32 = 1 } ta_dtype;
  *                      ELEMENTS and must keep every row 16-byte aligned
  *                      (stride_n >= d).  A whole [N,d] head slice must span
  *                      less than 4 GiB.
- *   d in {64, 128};  Hq % Hkv == 0;  1 <= Hq / Hkv <= 16.
+ *   d in {64, 128};  Hq % Hkv == 0 (any group size Hq / Hkv, multi-query included).
  * bf16 inputs: scores and all sums are accumulated in fp32.
  * fp32 inputs: scores and the running max are accumulated in fp64, the
  *              exponentials and sums in fp32.

@@ -1,6 +1,7 @@
-// decode_partial on the matrix cores: bf16 K/V, d = 128 or 64, up to 16 query
-// heads per KV head in one pass (the layout notes below are written for d = 128;
-// Geo<D> holds what changes at d = 64: 64-bit row loads, 2 k-steps, 4 PV tiles).  Same contract as the VALU kernel in
+// decode_partial on the matrix cores: bf16 K/V, d = 128 or 64, up to 64
+// (query token, head) pairs per KV head in one pass.  The layout notes below
+// are written for d = 128; Geo<D> holds what changes at d = 64 (64-bit row
+// loads, 2 k-steps, 4 PV tiles).  Same contract as the VALU kernel in
 // decode_partial.hip (Tree Attention, arXiv 2408.04093, Algorithm 3 steps 1-2:
 // per-chunk partial (m, l, o); Section 3 recurrence with the Appendix F max
 // shift), different arithmetic engine.
@@ -123,14 +124,14 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     const int64_t lo = rg.lo;
     const int n = rg.n;
 
-    // MFMA rows: row = (local token) * g + (head in group); this workgroup owns
-    // query tokens [t0, t0 + ntok) of the Sq (one token in plain decode)
-    const int t0 = rg.slice * a.tq;
-    const int ntok = (a.Sq - t0) < a.tq ? (a.Sq - t0) : a.tq;
-    const int nrows = ntok * g;                 // <= 16 * NRB
+    // MFMA rows: the (token, head in group) pairs of this kv head, numbered token-major
+    // (token * g + head in group); this workgroup owns rows [r0, r0 + nrows), which may start
+    // and end inside a token
+    const int r0 = rg.slice * a.rows;
+    const int nrows = (a.Sq * g - r0) < a.rows ? (a.Sq * g - r0) : a.rows;   // <= 16 * NRB
     const int HqV = a.Sq * a.Hq;                // (token, head) pairs per sequence
     // virtual head of a row: token-major [Sq][Hq]
-    auto vhead = [&](int row) { return (t0 + row / g) * a.Hq + hk * g + row % g; };
+    auto vhead = [&](int row) { return ((r0 + row) / g) * a.Hq + hk * g + (r0 + row) % g; };
     // index of a row's partial: [B, Sq*Hq, P] in a chunked launch, [piece, piece_rows] in a balanced one
     auto pindex = [&](int row) -> int64_t {
         if constexpr (BALANCED) return rg.slot * a.piece_rows + row;
@@ -173,7 +174,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     for (int rb = 0; rb < NRB; ++rb) {
         const int row = 16 * rb + c;
         my_row[rb] = row < nrows ? row : 0;
-        const int64_t lim = rg.L - a.Sq + 1 + (t0 + my_row[rb] / g) - lo;
+        const int64_t lim = rg.L - a.Sq + 1 + (r0 + my_row[rb]) / g - lo;
         nlim[rb] = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
         const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row[rb])) * D + 8 * r) * 2;
 #pragma unroll
@@ -185,7 +186,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     }
     int n_common;   // keys every row may use: steps below it need no masking
     {
-        const int64_t limc = rg.L - a.Sq + 1 + t0 - lo;
+        const int64_t limc = rg.L - a.Sq + 1 + r0 / g - lo;
         n_common = (int)(limc < 0 ? 0 : (limc > n ? n : limc));
     }
 
@@ -624,7 +625,7 @@ hipError_t launch_mode(const PartialArgs &a, int mode, dim3 grid, hipStream_t s)
 template <int D>
 hipError_t launch_rows(const PartialArgs &a, int mode, hipStream_t s) {
     const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
-    const int rows = a.tq * a.g;
+    const int rows = a.rows;
     if (rows <= 16) return launch_mode<D, 1>(a, mode, grid, s);
     if (rows <= 32) return launch_mode<D, 2>(a, mode, grid, s);
     return launch_mode<D, 4>(a, mode, grid, s);
@@ -639,7 +640,7 @@ hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hip
 template <int D>
 hipError_t launch_balanced(const PartialArgs &a, hipStream_t s) {
     const dim3 grid((uint32_t)a.W);
-    const int rows = a.tq * a.g;
+    const int rows = a.rows;
     if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
     else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 2>), grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);

@@ -13,18 +13,18 @@ using namespace ta;
 
 inline int elem_bytes(int dt) { return dt == TA_BF16 ? 2 : 4; }
 inline int tokens(const ta_problem *p) { return p->Sq > 1 ? p->Sq : 1; }
-// query tokens per workgroup on the matrix-core kernel: (token, head) pairs fill up to 4 blocks of
-// 16 MFMA rows that share one pass over K/V
-inline int tokens_per_workgroup(const ta_problem *p) {
-    const int tq = 64 / (p->Hq / p->Hkv);
-    return tq < tokens(p) ? tq : tokens(p);
+// Matrix-core kernel: the (token, head-in-group) pairs of one kv head are numbered token-major and
+// cut into slices of up to 64 rows (4 blocks of 16 MFMA rows); a slice shares one pass over K/V
+constexpr int kMaxRows = 64;
+inline int64_t total_rows(const ta_problem *p) { return (int64_t)tokens(p) * (p->Hq / p->Hkv); }
+inline int rows_per_slice(const ta_problem *p) {
+    return (int)(total_rows(p) < kMaxRows ? total_rows(p) : kMaxRows);
 }
 // independent workgroup groups per chunk index
 inline int64_t launch_groups(const ta_problem *p) {
     const int g = p->Hq / p->Hkv;
     if (use_mfma_path(p->qkv_dtype, p->d)) {
-        const int tq = tokens_per_workgroup(p);
-        return (int64_t)p->B * p->Hkv * ((tokens(p) + tq - 1) / tq);
+        return (int64_t)p->B * p->Hkv * ((total_rows(p) + kMaxRows - 1) / kMaxRows);
     }
     return (int64_t)p->B * p->Hkv * (g / heads_per_workgroup(p->qkv_dtype, p->d, g));
 }
@@ -38,7 +38,6 @@ ta_status check_problem(const ta_problem *p) {
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1) return TA_ERR_SHAPE;
     if (p->Hq % p->Hkv != 0) return TA_ERR_SHAPE;
     if (p->d != 64 && p->d != 128) return TA_ERR_UNSUPPORTED;
-    if (p->Hq / p->Hkv > 16) return TA_ERR_UNSUPPORTED;
     if (!std::isfinite(p->scale)) return TA_ERR_SHAPE;
     const int eb = elem_bytes(p->qkv_dtype);
     const int64_t strides[6] = {p->k_stride_b, p->k_stride_h, p->k_stride_n,
@@ -148,7 +147,7 @@ BalancedPlan balanced_plan(const ta_problem *p, int cus) {
     const int64_t groups = launch_groups(p);
     b.W = cus;
     b.pieces = b.W + groups;
-    b.rows = tokens_per_workgroup(p) * (p->Hq / p->Hkv);
+    b.rows = rows_per_slice(p);
     const size_t slots = (size_t)b.pieces * b.rows;
     b.off_m = slots * p->d * sizeof(float);
     b.off_l = b.off_m + slots * sizeof(float);
@@ -182,7 +181,7 @@ PartialArgs base_args(const ta_problem *p, const void *q, const void *K, const v
     a.B = p->B; a.Hq = p->Hq; a.Hkv = p->Hkv; a.P = 1;
     a.g = p->Hq / p->Hkv;
     a.Sq = tokens(p);
-    a.tq = tokens_per_workgroup(p);
+    a.rows = rows_per_slice(p);
     a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
     a.c = (double)p->scale * kLog2e;
     return a;
@@ -307,7 +306,7 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
         c.out_dtype = p->out_dtype;
         c.cum = a.cum;
         c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
-        c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.tq = a.tq;
+        c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.rows = a.rows;
         return launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
     }
     if (P == 1 && use_mfma_path(p->qkv_dtype, p->d)) {

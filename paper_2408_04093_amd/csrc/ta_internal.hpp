@@ -24,7 +24,7 @@ struct PartialArgs {
     int32_t out_dtype;
     // balanced launch (matrix-core kernel, ragged batches): W workgroups share all keys equally
     int32_t W;                  // workgroups = shares
-    int32_t piece_rows;         // rows reserved per piece in the partial arrays (tq * g)
+    int32_t piece_rows;         // rows reserved per piece in the partial arrays (= rows)
     int64_t *cum;               // device [B+1]: prefix sums of the virtual lengths (keys + piece charge),
                                 // written by workgroup 0 for the combine kernel
     int64_t N;
@@ -33,9 +33,10 @@ struct PartialArgs {
     uint32_t k_row_bytes, v_row_bytes;
     int32_t B, Hq, Hkv, P;
     int32_t g;                  // Hq / Hkv
-    int32_t slices;             // VALU kernel: g / heads-per-workgroup; MFMA kernel: token slices
+    int32_t slices;             // VALU kernel: g / heads-per-workgroup; MFMA kernel: row slices
     int32_t Sq;                 // query tokens per sequence (>= 1)
-    int32_t tq;                 // MFMA kernel: query tokens per workgroup, tq * g <= 16
+    int32_t rows;               // MFMA kernel: (token, head-in-group) rows per slice, <= 64.  Rows are numbered
+                                // token-major (row = token * g + head in group) and cut into slices of `rows`
     double c;                   // scale * log2(e)
 };
 
@@ -48,7 +49,7 @@ struct CombineArgs {
     // balanced launch: the partials of row (b, t, h) are the consecutive pieces of its segment
     const int64_t *cum;         // null = chunked layout [B,Hq,P]
     int32_t W, min_share, piece_cost, piece_rows;
-    int32_t heads, g, Hkv, slices, tq;   // real Hq, group size, kv heads, token slices, tokens per slice
+    int32_t heads, g, Hkv, slices, rows; // real Hq, group size, kv heads, row slices, rows per slice
 };
 // energy pass: lse from (m, l) partials only; gradient pass: out = plain sum of the partial numerators
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s);

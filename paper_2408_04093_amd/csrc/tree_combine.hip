@@ -62,9 +62,10 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
     if (a.cum) {
         const int b = (int)(bh / a.Hq), vrow = (int)(bh % a.Hq);
         const int t = vrow / a.heads, hq = vrow % a.heads;
-        const int row = (t % a.tq) * a.g + hq % a.g;
+        const int grow = t * a.g + hq % a.g;            // row number inside the kv head, token-major
+        const int row = grow % a.rows;
         const int64_t G = (int64_t)a.Hkv * a.slices;
-        const int64_t j = (int64_t)(hq / a.g) * a.slices + t / a.tq;
+        const int64_t j = (int64_t)(hq / a.g) * a.slices + grow / a.rows;
         // cum holds virtual lengths: keys + piece_cost per non-empty segment, the keys coming last
         const int64_t Lv = a.cum[b + 1] - a.cum[b];
         const int64_t Lb = Lv - a.piece_cost;

@@ -85,7 +85,6 @@ def test_workspace_and_chunk_heuristic(lib):
 @pytest.mark.parametrize("mutate,code", [
     (lambda p: setattr(p, "d", 96), 6),
     (lambda p: setattr(p, "Hq", 30), 2),
-    (lambda p: setattr(p, "Hkv", 1), 6),             # group of 32 heads
     (lambda p: setattr(p, "N", 0), 2),
     (lambda p: setattr(p, "qkv_dtype", 7), 3),
     (lambda p: setattr(p, "k_stride_n", 132), 4),    # rows no longer 16-byte aligned
@@ -93,7 +92,7 @@ def test_workspace_and_chunk_heuristic(lib):
     (lambda p: setattr(p, "scale", float("nan")), 2),
     (lambda p: setattr(p, "N", 1 << 25), 6),         # head slice >= 4 GiB
     (lambda p: setattr(p, "Sq", -1), 2),
-    (lambda p: (setattr(p, "Sq", 4), setattr(p, "qkv_dtype", 1)), 6),   # several tokens need bf16, d = 128
+    (lambda p: (setattr(p, "Sq", 4), setattr(p, "qkv_dtype", 1)), 6),   # several tokens need bf16
 ])
 def test_bad_problems_are_refused_before_launch(lib, mutate, code):
     p = llama_problem()

@@ -148,6 +148,10 @@ SHAPES = [
     ("bf16", 1, 16, 1, 64, 4099), ("bf16", 2, 12, 2, 64, 257), ("bf16", 2, 3, 1, 64, 1), ("bf16", 1, 2, 2, 64, 777),
     ("f32", 1, 1, 1, 64, 1025), ("f32", 2, 4, 2, 64, 300), ("f32", 1, 8, 1, 64, 200),
     ("f32", 1, 2, 1, 128, 519), ("f32", 1, 4, 1, 128, 64), ("f32", 1, 1, 1, 128, 7),
+    # multi-query and wide groups: 17..64 heads ride on one pass, beyond that slices of 64 rows
+    ("bf16", 1, 32, 1, 128, 1500), ("bf16", 1, 48, 1, 128, 777), ("bf16", 1, 71, 1, 64, 900),
+    ("bf16", 2, 40, 2, 128, 300), ("bf16", 1, 128, 1, 128, 400), ("bf16", 1, 130, 2, 64, 333),
+    ("f32", 1, 24, 1, 64, 300), ("f32", 1, 71, 1, 128, 100),
 ]
 
 
@@ -447,7 +451,9 @@ def check_multi(w):
     (1, 16, 32, 8, 1500), (1, 5, 8, 1, 900), (2, 20, 4, 1, 700), (1, 5, 16, 1, 333), (1, 40, 2, 2, 400),
     # d = 64: one, two and four row blocks, and token slices
     (2, 4, 8, 2, 1000, 64), (1, 3, 8, 1, 513, 64), (1, 16, 32, 8, 1500, 64), (1, 5, 16, 1, 333, 64),
-    (2, 20, 4, 1, 700, 64), (1, 7, 12, 2, 2048, 64)]])
+    (2, 20, 4, 1, 700, 64), (1, 7, 12, 2, 2048, 64),
+    # groups wider than 16: slices of 64 rows start and end inside a token
+    (1, 5, 20, 1, 600), (2, 3, 48, 2, 500), (1, 4, 71, 1, 450, 64), (1, 2, 64, 1, 300), (1, 3, 100, 1, 200)]])
 def test_multi_token_causal_decode(B, Sq, Hq, Hkv, N, d):
     w = W.make_multi(B, Sq, Hq, Hkv, d, N, torch.bfloat16, seed=77 + Sq + N, device="cuda")
     check_multi(w)
@@ -533,7 +539,7 @@ def test_graph_capture_and_replay():
 @pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [(1, 1, 4, 1, 1), (2, 1, 8, 2, 1000), (1, 1, 16, 1, 4099),
                                             (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000), (1, 12, 8, 2, 600),
-                                            (1, 9, 16, 2, 450)])
+                                            (1, 9, 16, 2, 450), (1, 1, 48, 1, 900), (2, 3, 40, 1, 350)])
 def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N, d):
     if Sq == 1:
         w = W.make_qkv(B, Hq, Hkv, d, N, torch.bfloat16, seed=300 + N, device="cuda")
@@ -658,6 +664,12 @@ def test_skewed_ragged_batch_is_balanced_over_the_device(d):
     wm = W.make_multi(3, 9, 16, 1, d, 2000, torch.bfloat16, seed=83, device="cuda")   # g = 16: 4 + 4 + 1 tokens
     wm.valid_len = torch.tensor([2000, 8, 1234], dtype=torch.int32, device="cuda")
     check_multi(wm)
+    wm = W.make_multi(4, 3, 48, 2, d, 3000, torch.bfloat16, seed=86, device="cuda")   # g = 24: 72 rows, 64 + 8
+    wm.valid_len = torch.tensor([3000, 2, 0, 1500], dtype=torch.int32, device="cuda")
+    check_multi(wm)
+    w = W.make_qkv(5, 71, 1, d, 5000, torch.bfloat16, seed=87, device="cuda")       # multi-query, 71 heads
+    w.valid_len = torch.tensor([5000, 17, 0, 2500, 1], dtype=torch.int32, device="cuda")
+    check(w)
 
 
 def test_ragged_batch_with_no_keys_at_all():
