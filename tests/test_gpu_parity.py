@@ -428,6 +428,38 @@ def test_paper_shard_shapes_full(N):
     check(w)
 
 
+def test_algorithm3_device_level_form_rehearsed_with_shards_on_one_gpu():
+    """Algorithm 3 as the paper states it: p devices each hold a shard of K/V and compute the
+    normalised (o_j, lse_j) of their shard (here: ta_decode on each shard in turn), then
+    m = max_j lse_j, out = sum_j o_j e^(lse_j - m) / sum_j e^(lse_j - m).  In (m, l, o) terms a device's
+    result is the partial (lse_j, 1, o_j), so the all-reduce arithmetic is ta_tree_combine itself."""
+    p_dev, B, Hq, Hkv, d, N = 8, 2, 16, 4, 128, 8 * 4000 + 123           # unequal last shard
+    w = W.make_qkv(B, Hq, Hkv, d, N, torch.bfloat16, seed=401, device="cuda")
+    w.valid_len = torch.tensor([N, 9000], dtype=torch.int32, device="cuda")   # devices 3..7 hold nothing of b = 1
+    cuts = [min(N, 4000 * j) for j in range(p_dev)] + [N]
+    outs, lses = [], []
+    for j in range(p_dev):
+        lo, hi = cuts[j], cuts[j + 1]
+        vl = (w.valid_len - lo).clamp(0, hi - lo).to(torch.int32)
+        o, l = ta.decode(w.q, w.K[:, :, lo:hi], w.V[:, :, lo:hi], w.scale, vl, ta.TA_F32)
+        outs.append(o); lses.append(l)
+    part_o = torch.stack(outs, dim=2).contiguous()                          # [B,Hq,p,d]
+    part_m = torch.stack(lses, dim=2).contiguous()                          # [B,Hq,p]
+    part_l = torch.isfinite(part_m).to(torch.float32)                       # 1, or 0 for a device with no keys
+    out, lse = ta.tree_combine(part_m, part_l, part_o, ta.TA_F32)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    # and against the oracle's own Algorithm 3 steps 3-6 on the same per-device results
+    po, pm = part_o.cpu().numpy().astype(np.float64), part_m.cpu().numpy().astype(np.float64)
+    for (b, h) in [(0, 0), (0, 15), (1, 7)]:
+        live = np.isfinite(pm[b, h])
+        ro, rl = oracle.combine_alg3(po[b, h][live], pm[b, h][live])
+        assert row_rel_l2(out[b, h].cpu().numpy(), ro) <= 2e-6
+        assert abs(lse[b, h].item() - rl) <= 1e-5
+
+
 # ------------------------------------------------------------------ several query tokens, causal among them
 def check_multi(w):
     vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
