@@ -33,6 +33,8 @@
 //       cost ~1e-3 relative error in the output.
 // The contraction order of keys inside a tile is a fixed permutation
 // (kappa below) applied to P and V alike.
+#include <type_traits>
+
 #include "chunking.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
@@ -49,10 +51,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef TA_AUX
 #define TA_AUX 2   // non-temporal K/V loads
 #endif
-#ifndef TA_DEPTH
-#define TA_DEPTH 1 // register tiles (steps of K and V) kept in flight per wave
-#endif
 
+#ifndef TA_WPE
+#define TA_WPE(nrb) ((nrb) == 1 ? 2 : 1)   // waves per SIMD the register budget is sized for
+#endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kTile = 32;                       // keys per wave step
@@ -97,6 +99,19 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
 // K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
 enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 
+// Per-wave row statistics handed through LDS when the waves of a workgroup are merged.
+struct WaveStats {
+    float m[kWaves][kMaxHeads];   // shift the wave's l and o are relative to (log2 units)
+    float t[kWaves][kMaxHeads];   // true row maximum seen by the wave
+    float l[kWaves][kMaxHeads];   // normaliser
+};
+
+// The running shift of a row is raised only when a step's row maximum exceeds it by more than
+// this many log2 units, so exponentials stay below 2^kLazy.  Raising on every new maximum is
+// not rare: with R rows riding on a wave, step t brings a new maximum for some row with
+// probability ~R/t, i.e. on most steps of a 4096-key chunk once 16 or more rows are live.
+constexpr float kLazy = 8.0f;
+
 // Where one range of keys of one (batch, kv head, token slice) goes.
 struct Range {
     int b, hk, slice;
@@ -107,10 +122,10 @@ struct Range {
 };
 
 // The whole streaming computation for one range: called once per workgroup by the chunked kernel
-// and once per piece by the balanced kernel.  smem / lds_m / lds_l are the workgroup's LDS areas.
+// and once per piece by the balanced kernel.  smem / st are the workgroup's LDS areas.
 template <int D, int MODE, int NRB, bool BALANCED>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &rg, char *smem,
-                                              float (*lds_m)[kMaxHeads], float (*lds_l)[kMaxHeads]) {
+                                              WaveStats &st) {
     using G_ = Geo<D>;
     using row_t = typename G_::row_t;
     constexpr int kCols = G_::kCols, kSteps = G_::kSteps, kPitch = G_::kPitch, kStage = G_::kStage;
@@ -211,12 +226,21 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     }
     char *stage = smem + w * kStage;
 
+    // loads of a full tile: no branch, so that the steady-state loop below has one fixed pattern
+    // of outstanding loads and every wait can be exact
+    auto issue_k_full = [&](row_t (&kr)[8], int it) {
+        const uint32_t inc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kr[e] = G_::load(krs, (int)(koff[e] + inc));
+    };
+    auto issue_v_full = [&](row_t (&vr)[8], int it) {
+        const uint32_t inc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vr[e] = G_::load(vrs, (int)(voff[e] + inc));
+    };
     auto issue_k = [&](row_t (&kr)[8], int it) {
         if (it < n_full) {
-            const uint32_t inc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                kr[e] = G_::load(krs, (int)(koff[e] + inc));
+            issue_k_full(kr, it);
         } else {   // ragged last steps: rows past the chunk are redirected to its last row
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -228,10 +252,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     };
     auto issue_v = [&](row_t (&vr)[8], int it) {
         if (it < n_full) {
-            const uint32_t inc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                vr[e] = G_::load(vrs, (int)(voff[e] + inc));
+            issue_v_full(vr, it);
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -243,12 +264,14 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     };
 
     const float cs = (float)a.c;   // scale * log2(e)
-    float m_run[NRB];              // running max of this lane's row (log2 units), same in all 4 row groups
+    float m_run[NRB];              // shift of this lane's row (log2 units): a past row maximum, at most kLazy
+                                   // below the current one; same in all 4 row groups
+    float m_true[NRB];             // true running maximum of the row
     float l_run[NRB];              // this lane's share of the row's normaliser
     f32x4 acc[NRB][kCols];         // acc[rb][j][i] = O[row 16rb + 4r + i][col kCols c + j]
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        m_run[rb] = -__builtin_huge_valf();
+        m_run[rb] = m_true[rb] = -__builtin_huge_valf();
         l_run[rb] = 0.f;
         if constexpr (MODE == kGradient) {
             // the shift is the given total logsumexp (natural log -> log2 units); a row with no key
@@ -260,15 +283,26 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         for (int j = 0; j < kCols; ++j) acc[rb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // One pipeline step on the register tiles (kr, vr) holding step `it`; the tiles are refilled
-    // with step it + TA_DEPTH as soon as they have been consumed.
-    auto step = [&](row_t (&kr)[8], row_t (&vr)[8], int it) {
-        const bool masked = it >= n_full;
+    // One pipeline step on the register tiles (kr, vr) holding step `it`, in two halves around the
+    // only data-dependent decision, whether a running max must be raised:
+    //   front: K tile to LDS, next K tile in flight, S = K Q^T, scaled (and masked) scores, row maxima
+    //   back:  exponentials, P, O += P V, next V tile in flight
+    // TAIL is a compile-time flag (std::true_type / std::false_type).  Steady steps (TAIL false) are
+    // full tiles followed by another full tile: no masking arithmetic, and the next tile's loads are
+    // issued unconditionally.  Tail steps mask rows beyond each row's limit and issue the next tile
+    // only if there is one.
+    float sv[NRB][8];   // scaled scores of the current step (log2 units), slot e = 4G + i
+    float mx[NRB];      // row maxima of the current step
+    bool up[NRB];
+
+    auto front = [&](auto tail_c, row_t (&kr)[8], int it) -> bool {
+        constexpr bool masked = decltype(tail_c)::value;
         // ---- K tile: registers -> LDS (row-major, padded) -> A layout
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             *reinterpret_cast<row_t *>(stage + trow[e] * kPitch + c * kLaneBytes) = kr[e];
-        if (it + TA_DEPTH < n_iters) issue_k(kr, it + TA_DEPTH);
+        if constexpr (!masked) issue_k_full(kr, it + 1);
+        else if (it + 1 < n_iters) issue_k(kr, it + 1);
 
         // S = K Q^T.  The 2 key groups x NRB row blocks are independent accumulation chains; the
         // k-step loop is outermost so that consecutive MFMAs never depend on each other.
@@ -290,19 +324,17 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                     s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[G][t]), qb[rb][t],
                                                                         s[rb][G], 0, 0, 0);
 
-        // ---- online softmax: per row block this lane owns 8 keys (slot e = 4G + i) of one row.
-        // Done in phases over all row blocks (scores and row max; one shared decision whether any
-        // running max must be raised; exponentials) so that the blocks' dependency chains interleave.
-        float sv[NRB][8];
-        bool up[NRB];
-        float mx[NRB];
+        // per row block this lane owns 8 keys of one row.  Done in phases over all row blocks
+        // (scores and lane max; the two cross-lane steps of the row max) so that the blocks'
+        // dependency chains interleave.
         bool any_up = false;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 sv[rb][e] = s[rb][e >> 2][e & 3] * cs;
-                if (masked && it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[rb][e] = -__builtin_huge_valf();
+                if constexpr (masked)
+                    if (it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[rb][e] = -__builtin_huge_valf();
             }
             if constexpr (MODE != kGradient) {
                 float m8 = sv[rb][0];
@@ -317,28 +349,64 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) {
                 mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 32));
-                up[rb] = mx[rb] > m_run[rb];
+                m_true[rb] = fmaxf(m_true[rb], mx[rb]);
+                up[rb] = mx[rb] > m_run[rb] + kLazy;   // also true on a row's first keys (-inf + kLazy = -inf)
                 any_up |= up[rb];
             }
-            if (__builtin_amdgcn_ballot_w64(any_up) != 0) {
-                // raise running maxima: rare once the stream is warm
+            return __builtin_amdgcn_ballot_w64(any_up) != 0;
+        }
+        return false;
+    };
+
+    // move the shifts up to the current step's row maxima: after a row's first keys this only
+    // happens when its scores jump by more than kLazy
+    auto raise = [&]() {
 #pragma unroll
-                for (int rb = 0; rb < NRB; ++rb) {
-                    const float alpha = up[rb] ? exp2_hw(m_run[rb] - mx[rb]) : 1.0f;
-                    m_run[rb] = up[rb] ? mx[rb] : m_run[rb];
-                    l_run[rb] *= alpha;
-                    if constexpr (MODE == kFull) {
-                        // acc[rb][.][i] belongs to row 4r+i of the block, whose alpha sits in lane (r, 4r+i)
+        for (int rb = 0; rb < NRB; ++rb) {
+            const float alpha = up[rb] ? exp2_hw(m_run[rb] - mx[rb]) : 1.0f;
+            m_run[rb] = up[rb] ? mx[rb] : m_run[rb];
+            l_run[rb] *= alpha;
+            if constexpr (MODE == kFull) {
+                // acc[rb][.][i] belongs to row 4r+i of the block, whose alpha sits in lane (r, 4r+i)
+                float ai[4];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float ai = __shfl(alpha, (lane & 48) | (4 * r + i));
+                for (int i = 0; i < 4; ++i) ai[i] = __shfl(alpha, (lane & 48) | (4 * r + i));
+                if constexpr (NRB == 1) {
+                    // the single-block kernels keep everything in vector registers: scale in place
 #pragma unroll
-                            for (int j = 0; j < kCols; ++j) acc[rb][j][i] *= ai;
-                        }
+                    for (int j = 0; j < kCols; ++j)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[rb][j][i] *= ai[i];
+                } else {
+                    // With more row blocks the accumulators live in accumulation registers, which only
+                    // MFMAs and memory instructions can address.  They are stored to the wave's K
+                    // staging area (free here: S has been computed), scaled there through temporaries,
+                    // and loaded back, so that no vector-ALU instruction ever reads or defines an
+                    // accumulator inside the loop; otherwise the register allocator keeps a
+                    // vector-register copy of all of them and moves them back and forth on every
+                    // step.  Each lane reads only what it wrote: no barrier needed.
+                    f32x4 *bounce = reinterpret_cast<f32x4 *>(stage) + lane;
+#pragma unroll
+                    for (int j = 0; j < kCols; ++j) bounce[j * kWave] = acc[rb][j];
+                    asm volatile("" ::: "memory");   // keeps loads from being forwarded from the stores
+#pragma unroll
+                    for (int j = 0; j < kCols; ++j) {
+                        f32x4 t = bounce[j * kWave];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) t[i] *= ai[i];
+                        bounce[j * kWave] = t;
                     }
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int j = 0; j < kCols; ++j) acc[rb][j] = bounce[j * kWave];
+                    asm volatile("" ::: "memory");
                 }
             }
         }
+    };
+
+    auto back = [&](auto tail_c, row_t (&vr)[8], int it) {
+        constexpr bool masked = decltype(tail_c)::value;
         bf16x8 pa_hi[NRB], pa_lo[NRB];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -346,7 +414,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 p[e] = exp2_hw(sv[rb][e] - m_run[rb]);
-                if (masked && sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;
+                if constexpr (masked)
+                    if (sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;   // also when m_run is still -inf
                 l_run[rb] += p[e];
             }
             if constexpr (MODE != kEnergy) {
@@ -382,24 +451,36 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 for (int rb = 0; rb < NRB; ++rb)
                     acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo[rb], vbj, acc[rb][j], 0, 0, 0);
             }
-            if (it + TA_DEPTH < n_iters) issue_v(vr, it + TA_DEPTH);
+            if constexpr (!masked) issue_v_full(vr, it + 1);
+            else if (it + 1 < n_iters) issue_v(vr, it + 1);
         }
     };
 
-    // TA_DEPTH register tiles in rotation (1 measured as good as 2 or 3: the stream is DRAM-bound,
-    // not latency-bound, and one tile keeps two workgroups resident per CU)
-    row_t kr[TA_DEPTH][8], vr[TA_DEPTH][8];
-#pragma unroll
-    for (int x = 0; x < TA_DEPTH; ++x) {
-        if (x < n_iters) {
-            issue_k(kr[x], x);
-            if constexpr (MODE != kEnergy) issue_v(vr[x], x);
+    // One register tile of K and one of V per wave, refilled with the next step as soon as it has
+    // been consumed (two or three tiles in rotation measured no faster).  The steady-state loop is
+    // entered with exactly the pattern of outstanding loads it leaves behind on every step (K tile,
+    // then V tile), so the compiler's wait counts are exact: waiting for K leaves V in flight and
+    // waiting for V leaves the next K in flight.
+    row_t kr[8], vr[8];
+    const int n_steady = n_full > 0 ? n_full - 1 : 0;   // full tiles whose successor is a full tile too
+    int it = 0;
+    if (n_steady > 0) {
+        issue_k_full(kr, 0);
+        // the K loads must be the older ones, as on every later step: without the barrier the
+        // scheduler is free to issue V first, and the wait counts of the whole loop follow the entry
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MODE != kEnergy) issue_v_full(vr, 0);
+        for (; it < n_steady; ++it) {
+            if (front(std::false_type{}, kr, it)) raise();
+            back(std::false_type{}, vr, it);
         }
+    } else {
+        issue_k(kr, 0);
+        if constexpr (MODE != kEnergy) issue_v(vr, 0);
     }
-    for (int it = 0; it < n_iters; it += TA_DEPTH) {
-#pragma unroll
-        for (int x = 0; x < TA_DEPTH; ++x)
-            if (it + x < n_iters) step(kr[x], vr[x], it + x);
+    for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
+        if (front(std::true_type{}, kr, it)) raise();
+        back(std::true_type{}, vr, it);
     }
 
     // ---- merge the waves through LDS, one row block at a time (the K staging area is free now)
@@ -424,8 +505,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             }
         }
         if (r == 0 && c < brows) {
-            lds_m[w][c] = m_run[rb];
-            lds_l[w][c] = lw;
+            st.m[w][c] = m_run[rb];
+            st.t[w][c] = m_true[rb];
+            st.l[w][c] = lw;
         }
         __syncthreads();
 
@@ -441,9 +523,12 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         } else {
             const int col = MODE == kEnergy ? 0 : tid % D;
             for (int h = MODE == kEnergy ? tid : tid / D; h < brows; h += MODE == kEnergy ? kThreads : kThreads / D) {
-                float ms = lds_m[0][h];
+                float ms = st.m[0][h], mt = st.t[0][h];   // common shift of the merge, true maximum
 #pragma unroll
-                for (int ww = 1; ww < kWaves; ++ww) ms = fmaxf(ms, lds_m[ww][h]);
+                for (int ww = 1; ww < kWaves; ++ww) {
+                    ms = fmaxf(ms, st.m[ww][h]);
+                    mt = fmaxf(mt, st.t[ww][h]);
+                }
                 const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
                 const int64_t pidx = pindex(16 * rb + h);
                 if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
@@ -465,9 +550,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 float lt = 0.f, ot = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww) {
-                    const float mw = lds_m[ww][h];
+                    const float mw = st.m[ww][h];
                     const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
-                    lt = fmaf(f, lds_l[ww][h], lt);
+                    lt = fmaf(f, st.l[ww][h], lt);
                     if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * 16 + h) * D + col], ot);
                 }
                 if (direct) {   // single chunk: Algorithm 3 step 6 right here
@@ -479,8 +564,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                     if (col == 0) a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
                     continue;
                 }
-                // natural-log units for the stored max; l and o follow the rounding of the stored value
-                const float m_nat = ms * (float)kLn2;
+                // the stored m is the true maximum in natural-log units; l and o, so far relative to the
+                // shift ms, are moved to the value actually stored (this also absorbs its rounding)
+                const float m_nat = mt * (float)kLn2;
                 const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
                 if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
                 if (col == 0) {
@@ -494,14 +580,13 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 
 // Chunked launch: one workgroup per (batch, kv head, token slice, chunk).
 template <int D, int MODE, int NRB>
-__global__ void __launch_bounds__(kThreads) decode_partial_mfma_kernel(const PartialArgs a) {
+__global__ void __launch_bounds__(kThreads, TA_WPE(NRB)) decode_partial_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
-    __shared__ float lds_m[kWaves][kMaxHeads];
-    __shared__ float lds_l[kWaves][kMaxHeads];
+    __shared__ WaveStats st;
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
-    process_range<D, MODE, NRB, false>(a, rg, smem, lds_m, lds_l);
+    process_range<D, MODE, NRB, false>(a, rg, smem, st);
 }
 
 // Balanced launch for ragged batches (lengths known only on the device).  The keys of all
@@ -520,10 +605,9 @@ constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many b
 constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
 
 template <int D, int NRB>
-__global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const PartialArgs a) {
+__global__ void __launch_bounds__(kThreads, TA_WPE(NRB)) decode_balanced_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
-    __shared__ float lds_m[kWaves][kMaxHeads];
-    __shared__ float lds_l[kWaves][kMaxHeads];
+    __shared__ WaveStats st;
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
     __shared__ int64_t sh_scan[kWaves];
     constexpr int kMinShare = kMinShareBytes / (2 * D), kPieceCost = kPieceCostBytes / (2 * D);   // in keys
@@ -604,7 +688,7 @@ __global__ void __launch_bounds__(kThreads) decode_balanced_mfma_kernel(const Pa
                            (int64_t)blockIdx.x + (int64_t)b * G + j};
             if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
             first = false;
-            process_range<D, kFull, NRB, true>(a, rg, smem, lds_m, lds_l);
+            process_range<D, kFull, NRB, true>(a, rg, smem, st);
         }
         x += span;
     }
