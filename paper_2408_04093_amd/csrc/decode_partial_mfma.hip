@@ -196,6 +196,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         for (int t = 0; t < kSteps; ++t) {
             v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
             if (row >= nrows) raw = v4i{0, 0, 0, 0};
+            // a negative scale is moved into q (flipping bf16 sign bits is exact), so that the
+            // multiplier below is >= 0 and the row maximum can be taken on unscaled scores
+            if (a.c < 0.0) raw ^= v4i{(int)0x80008000u, (int)0x80008000u, (int)0x80008000u, (int)0x80008000u};
             qb[rb][t] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -263,7 +266,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
     };
 
-    const float cs = (float)a.c;   // scale * log2(e)
+    const float cs = fabsf((float)a.c);   // |scale| * log2(e); the sign sits in q
     float m_run[NRB];              // shift of this lane's row (log2 units): a past row maximum, at most kLazy
                                    // below the current one; same in all 4 row groups
     float m_true[NRB];             // true running maximum of the row
@@ -291,8 +294,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // full tiles followed by another full tile: no masking arithmetic, and the next tile's loads are
     // issued unconditionally.  Tail steps mask rows beyond each row's limit and issue the next tile
     // only if there is one.
-    float sv[NRB][8];   // scaled scores of the current step (log2 units), slot e = 4G + i
-    float mx[NRB];      // row maxima of the current step
+    float sv[NRB][8];   // unscaled scores q.k of the current step, slot e = 4G + i (-inf where masked)
+    float mx[NRB];      // row maxima of the current step, scaled (log2 units)
     bool up[NRB];
 
     auto front = [&](auto tail_c, row_t (&kr)[8], int it) -> bool {
@@ -332,7 +335,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                sv[rb][e] = s[rb][e >> 2][e & 3] * cs;
+                sv[rb][e] = s[rb][e >> 2][e & 3];
                 if constexpr (masked)
                     if (it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[rb][e] = -__builtin_huge_valf();
             }
@@ -340,7 +343,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 float m8 = sv[rb][0];
 #pragma unroll
                 for (int e = 1; e < 8; ++e) m8 = fmaxf(m8, sv[rb][e]);
-                mx[rb] = m8;
+                mx[rb] = m8 * cs;
+                if constexpr (masked)
+                    if (m8 == -__builtin_huge_valf()) mx[rb] = m8;   // keeps -inf * 0 out when scale is 0
             }
         }
         if constexpr (MODE != kGradient) {
@@ -413,7 +418,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             float p[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                p[e] = exp2_hw(sv[rb][e] - m_run[rb]);
+                p[e] = exp2_hw(fmaf(sv[rb][e], cs, -m_run[rb]));
                 if constexpr (masked)
                     if (sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;   // also when m_run is still -inf
                 l_run[rb] += p[e];
@@ -440,8 +445,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 uint32_t bj[4];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
+                    // one byte permute: the low (j even) or high (j odd) halves of the two keys' registers
                     const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
-                    bj[x] = (j & 1) ? ((v0 >> 16) | (v1 & 0xffff0000u)) : ((v0 & 0xffffu) | (v1 << 16));
+                    bj[x] = __builtin_amdgcn_perm(v1, v0, (j & 1) ? 0x07060302u : 0x05040100u);
                 }
                 const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
 #pragma unroll
