@@ -72,9 +72,10 @@ struct Geo {
     static constexpr int kPitch = 2 * D + 16;       // LDS bytes per staged K row (16-byte pad: conflict-free A reads)
     static constexpr int kStage = kTile * kPitch;   // per wave
     typedef int row_t __attribute__((ext_vector_type(kWords)));   // one lane's share of one row
-    static __device__ __forceinline__ row_t load(__amdgpu_buffer_rsrc_t rs, int off) {
-        if constexpr (D == 128) return __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, TA_AUX);
-        else return __builtin_amdgcn_raw_buffer_load_b64(rs, off, 0, TA_AUX);
+    // off: per-lane byte offset (a vector register); soff: wave-uniform byte offset (a scalar register)
+    static __device__ __forceinline__ row_t load(__amdgpu_buffer_rsrc_t rs, int off, int soff = 0) {
+        if constexpr (D == 128) return __builtin_amdgcn_raw_buffer_load_b128(rs, off, soff, TA_AUX);
+        else return __builtin_amdgcn_raw_buffer_load_b64(rs, off, soff, TA_AUX);
     }
 };
 
@@ -104,6 +105,8 @@ struct WaveStats {
     float m[kWaves][kMaxHeads];   // shift the wave's l and o are relative to (log2 units)
     float t[kWaves][kMaxHeads];   // true row maximum seen by the wave
     float l[kWaves][kMaxHeads];   // normaliser
+    float f[kWaves][kMaxHeads];   // weight of the wave's numerators in the merged row
+    float fin[kMaxHeads];         // the merged row's final factor (partial) or normaliser (direct result)
 };
 
 // The running shift of a row is raised only when a step's row maximum exceeds it by more than
@@ -220,26 +223,25 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     const int n_full = n_common / ROWS_ITER;   // steps in which every key is visible to every row
 
     int trow[8];                // tile row of slot e for this lane
-    uint32_t koff[8], voff[8];  // byte offsets in iteration 0
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        trow[e] = kappa(r, e);
-        koff[e] = (uint32_t)(w * kTile + trow[e]) * a.k_row_bytes + c * kLaneBytes;
-        voff[e] = (uint32_t)(w * kTile + trow[e]) * a.v_row_bytes + c * kLaneBytes;
-    }
+    for (int e = 0; e < 8; ++e) trow[e] = kappa(r, e);
     char *stage = smem + w * kStage;
 
-    // loads of a full tile: no branch, so that the steady-state loop below has one fixed pattern
-    // of outstanding loads and every wait can be exact
+    // Loads of a full tile.  A lane's 8 rows are kappa(r, e) = 4r + (16 (e / 4) + e % 4): the lane part
+    // goes into one vector offset, the slot part and the step into the scalar offset of each load, so
+    // that a step costs no address arithmetic on the vector ALU.  No branch either: the steady-state
+    // loop below has one fixed pattern of outstanding loads and every wait can be exact.
+    const uint32_t klane = (uint32_t)(w * kTile + 4 * r) * a.k_row_bytes + c * kLaneBytes;
+    const uint32_t vlane = (uint32_t)(w * kTile + 4 * r) * a.v_row_bytes + c * kLaneBytes;
     auto issue_k_full = [&](row_t (&kr)[8], int it) {
-        const uint32_t inc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) kr[e] = G_::load(krs, (int)(koff[e] + inc));
+        for (int e = 0; e < 8; ++e)
+            kr[e] = G_::load(krs, (int)klane, (int)((uint32_t)(it * ROWS_ITER + 16 * (e >> 2) + (e & 3)) * a.k_row_bytes));
     };
     auto issue_v_full = [&](row_t (&vr)[8], int it) {
-        const uint32_t inc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vr[e] = G_::load(vrs, (int)(voff[e] + inc));
+        for (int e = 0; e < 8; ++e)
+            vr[e] = G_::load(vrs, (int)vlane, (int)((uint32_t)(it * ROWS_ITER + 16 * (e >> 2) + (e & 3)) * a.v_row_bytes));
     };
     auto issue_k = [&](row_t (&kr)[8], int it) {
         if (it < n_full) {
@@ -489,8 +491,13 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         back(std::true_type{}, vr, it);
     }
 
-    // ---- merge the waves through LDS, one row block at a time (the K staging area is free now)
+    // ---- merge the waves through LDS, one row block at a time (the K staging area is free now).
+    // Three phases per block: (1) every wave stores its numerators (all 16 rows, 128-bit stores)
+    // and row statistics; (2) one thread per row merges the statistics, stores the row's scalars
+    // and leaves the waves' weights and the row's final factor in LDS; (3) all threads sum the
+    // numerators column by column, with every LDS read of the unrolled row loop in flight at once.
     float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][16][D]
+    constexpr int kRowsPerPass = kThreads / D, kPasses = 16 / kRowsPerPass;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         const int brows = nrows - 16 * rb < 16 ? nrows - 16 * rb : 16;   // rows of this block
@@ -503,32 +510,23 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         if constexpr (MODE != kEnergy) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int h = 4 * r + i;
-                if (h < brows) {
+                float *dst = lds_o + (w * 16 + 4 * r + i) * D + kCols * c;
 #pragma unroll
-                    for (int j = 0; j < kCols; ++j) lds_o[(w * 16 + h) * D + kCols * c + j] = acc[rb][j][i];
-                }
+                for (int j = 0; j < kCols; j += 4)
+                    *reinterpret_cast<f32x4 *>(dst + j) =
+                        f32x4{acc[rb][j][i], acc[rb][j + 1][i], acc[rb][j + 2][i], acc[rb][j + 3][i]};
             }
         }
-        if (r == 0 && c < brows) {
+        if (r == 0) {
             st.m[w][c] = m_run[rb];
             st.t[w][c] = m_true[rb];
             st.l[w][c] = lw;
         }
         __syncthreads();
 
-        if constexpr (MODE == kGradient) {
-            // weights were already final: the waves' (and later the chunks') numerators simply add
-            const int col = tid % D;
-            for (int h = tid / D; h < brows; h += kThreads / D) {
-                float ot = 0.f;
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) ot += lds_o[(ww * 16 + h) * D + col];
-                a.part_o[pindex(16 * rb + h) * D + col] = ot;
-            }
-        } else {
-            const int col = MODE == kEnergy ? 0 : tid % D;
-            for (int h = MODE == kEnergy ? tid : tid / D; h < brows; h += MODE == kEnergy ? kThreads : kThreads / D) {
+        if constexpr (MODE != kGradient) {
+            if (tid < brows) {   // one thread per row
+                const int h = tid;
                 float ms = st.m[0][h], mt = st.t[0][h];   // common shift of the merge, true maximum
 #pragma unroll
                 for (int ww = 1; ww < kWaves; ++ww) {
@@ -537,47 +535,69 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 }
                 const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
                 const int64_t pidx = pindex(16 * rb + h);
+                float f[kWaves], lt = 0.f, fin;
                 if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
+#pragma unroll
+                    for (int ww = 0; ww < kWaves; ++ww) f[ww] = 0.f;
+                    fin = direct ? 1.0f : 0.f;        // numerators are all 0: out = 0 / 1, o = 0 * 0
                     if (direct) {
-                        if constexpr (MODE == kFull) {
-                            if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[vrow * D + col] = 0;
-                            else reinterpret_cast<float *>(a.out)[vrow * D + col] = 0.f;
-                        }
-                        if (col == 0) a.lse_out[vrow] = ms;
-                        continue;
-                    }
-                    if constexpr (MODE == kFull) a.part_o[pidx * D + col] = 0.f;
-                    if (col == 0) {
+                        a.lse_out[vrow] = ms;
+                    } else {
                         a.part_m[pidx] = ms;
                         a.part_l[pidx] = 0.f;
                     }
-                    continue;
+                } else {
+#pragma unroll
+                    for (int ww = 0; ww < kWaves; ++ww) {
+                        const float mw = st.m[ww][h];
+                        f[ww] = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
+                        lt = fmaf(f[ww], st.l[ww][h], lt);
+                    }
+                    if (direct) {   // single chunk: Algorithm 3 step 6 right here
+                        fin = lt;
+                        a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
+                    } else {
+                        // the stored m is the true maximum in natural-log units; l and o, so far relative
+                        // to the shift ms, are moved to the value actually stored (this also absorbs its
+                        // rounding)
+                        const float m_nat = mt * (float)kLn2;
+                        fin = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
+                        a.part_m[pidx] = m_nat;
+                        a.part_l[pidx] = lt * fin;
+                    }
                 }
-                float lt = 0.f, ot = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kWaves; ++ww) st.f[ww][h] = f[ww];
+                st.fin[h] = fin;
+            }
+            if constexpr (MODE == kFull) __syncthreads();
+        }
+
+        if constexpr (MODE != kEnergy) {
+            const int col = tid % D;
+#pragma unroll
+            for (int ps = 0; ps < kPasses; ++ps) {
+                const int h = tid / D + ps * kRowsPerPass;
+                const int hc = h < brows ? h : brows - 1;   // rows beyond the block repeat its last row, unstored
+                float ot = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < kWaves; ++ww) {
-                    const float mw = st.m[ww][h];
-                    const float f = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
-                    lt = fmaf(f, st.l[ww][h], lt);
-                    if constexpr (MODE == kFull) ot = fmaf(f, lds_o[(ww * 16 + h) * D + col], ot);
+                    const float x = lds_o[(ww * 16 + hc) * D + col];
+                    // gradient pass: weights were final all along, the waves' numerators simply add
+                    if constexpr (MODE == kGradient) ot += x;
+                    else ot = fmaf(st.f[ww][hc], x, ot);
                 }
-                if (direct) {   // single chunk: Algorithm 3 step 6 right here
-                    if constexpr (MODE == kFull) {
-                        const float z = ot / lt;
+                if (h < brows) {
+                    if constexpr (MODE == kGradient) {
+                        a.part_o[pindex(16 * rb + h) * D + col] = ot;
+                    } else if (direct) {
+                        const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
+                        const float z = ot / st.fin[hc];
                         if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[vrow * D + col] = f32_to_bf16_rne(z);
                         else reinterpret_cast<float *>(a.out)[vrow * D + col] = z;
+                    } else {
+                        a.part_o[pindex(16 * rb + h) * D + col] = ot * st.fin[hc];
                     }
-                    if (col == 0) a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
-                    continue;
-                }
-                // the stored m is the true maximum in natural-log units; l and o, so far relative to the
-                // shift ms, are moved to the value actually stored (this also absorbs its rounding)
-                const float m_nat = mt * (float)kLn2;
-                const float fix = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
-                if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
-                if (col == 0) {
-                    a.part_m[pidx] = m_nat;
-                    a.part_l[pidx] = lt * fix;
                 }
             }
         }
