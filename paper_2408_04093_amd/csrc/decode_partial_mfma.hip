@@ -186,7 +186,10 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // Per row block: the row this lane serves as "row lane" (row = 16 rb + c), its causal limit
     // (token t sees keys < L - Sq + 1 + t; chunk-relative, clamped to [0, n]) and its slice of
     // Q^T as MFMA B operand: lane (kb = r, row c) holds q[row][32t + 8r .. +8], zero for padding.
+    // The q loads are only issued here; their data is first touched (finish_q) after the first K
+    // and V tiles have been requested, so that the stream does not start one memory latency late.
     int my_row[NRB], nlim[NRB];
+    v4i qraw[NRB][kSteps];
     bf16x8 qb[NRB][kSteps];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
@@ -196,15 +199,23 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         nlim[rb] = (int)(lim < 0 ? 0 : (lim > n ? n : lim));
         const char *qp = (const char *)a.q + (((int64_t)b * HqV + vhead(my_row[rb])) * D + 8 * r) * 2;
 #pragma unroll
-        for (int t = 0; t < kSteps; ++t) {
-            v4i raw = *reinterpret_cast<const v4i *>(qp + 64 * t);
-            if (row >= nrows) raw = v4i{0, 0, 0, 0};
-            // a negative scale is moved into q (flipping bf16 sign bits is exact), so that the
-            // multiplier below is >= 0 and the row maximum can be taken on unscaled scores
-            if (a.c < 0.0) raw ^= v4i{(int)0x80008000u, (int)0x80008000u, (int)0x80008000u, (int)0x80008000u};
-            qb[rb][t] = __builtin_bit_cast(bf16x8, raw);
-        }
+        for (int t = 0; t < kSteps; ++t) qraw[rb][t] = *reinterpret_cast<const v4i *>(qp + 64 * t);
     }
+    auto finish_q = [&]() {
+        __builtin_amdgcn_sched_barrier(0);   // nothing that waits for q may move above the K/V requests
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) {
+                v4i raw = qraw[rb][t];
+                if (16 * rb + c >= nrows) raw = v4i{0, 0, 0, 0};
+                // a negative scale is moved into q (flipping bf16 sign bits is exact), so that the
+                // multiplier below is >= 0 and the row maximum can be taken on unscaled scores
+                if (a.c < 0.0) raw ^= v4i{(int)0x80008000u, (int)0x80008000u, (int)0x80008000u, (int)0x80008000u};
+                qb[rb][t] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
+    };
     int n_common;   // keys every row may use: steps below it need no masking
     {
         const int64_t limc = rg.L - a.Sq + 1 + r0 / g - lo;
@@ -478,6 +489,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         // scheduler is free to issue V first, and the wait counts of the whole loop follow the entry
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (MODE != kEnergy) issue_v_full(vr, 0);
+        finish_q();
         for (; it < n_steady; ++it) {
             if (front(std::false_type{}, kr, it)) raise();
             back(std::false_type{}, vr, it);
@@ -485,6 +497,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     } else {
         issue_k(kr, 0);
         if constexpr (MODE != kEnergy) issue_v(vr, 0);
+        finish_q();
     }
     for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
         if (front(std::true_type{}, kr, it)) raise();
