@@ -104,10 +104,10 @@ const char *ta_status_string(ta_status s);
  * Chunk count P that ta_decode uses for this problem on the current device.
  * Host-only heuristic: with equal work per chunk, one workgroup per compute
  * unit (P = CUs / (B * Hkv), more rounds only beyond 32768 keys per chunk);
- * for ragged batches or more (batch, kv head) groups than compute units,
- * chunks of a few thousand keys; never shorter than 256 keys; 1 when one
- * chunk per sequence already fills the device.  Returns 0 if the problem is
- * invalid.
+ * with more (batch, kv head) groups than compute units, the fewest chunks per
+ * sequence that fill the last round of workgroups, usually 1; for ragged
+ * batches beyond the reach of the balanced launch, chunks of a few thousand
+ * keys; never shorter than 256 keys.  Returns 0 if the problem is invalid.
  */
 int32_t ta_suggest_chunks(const ta_problem *p);
 

@@ -76,11 +76,14 @@ int device_compute_units() {
 // launch is ONE workgroup per compute unit, each streaming one long contiguous
 // share (7.2 TB/s at 1M keys; two per CU or a ragged last round measured
 // 4-8 % slower).  So P = CUs / groups, times a whole number of rounds only
-// when a chunk would exceed kLongChunk keys.  If there are more (batch, kv
-// head) groups than CUs, or the batch is ragged (lengths live on the device
-// and are unknown here), the work is cut fine enough (>= 8 workgroups per CU,
-// or chunks of kRaggedChunk keys: 4096 measured best on the ragged config, in
-// chunk-major launch order) for the hardware dispatcher to balance it.
+// when a chunk would exceed kLongChunk keys.  With more (batch, kv head)
+// groups than CUs two workgroups are resident per CU and long chunks win
+// (B = 64, N = 8192: P = 1 308 us, P = 4 318 us plus a combine): P is the
+// smallest count that fills the last round of workgroups, usually 1.  A
+// ragged batch too large for the balanced launch (lengths live on the device
+// and are unknown here) is cut into chunks of kRaggedChunk keys (4096
+// measured best on the ragged config, in chunk-major launch order) for the
+// hardware dispatcher to balance.
 //
 // VALU kernel (fp32): rounds of CUs x resident workgroups, chunks
 // near 4096 keys.
@@ -93,7 +96,7 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     if (use_mfma_path(p->qkv_dtype, p->d)) {
         // thresholds tuned at d = 128 in keys; what matters is bytes, so d = 64 doubles them
         const int64_t kd = 128 / p->d;
-        const int64_t kLongChunk = 32768 * kd, kRaggedChunk = 4096 * kd, kBalancedChunk = 2048 * kd;
+        const int64_t kLongChunk = 32768 * kd, kRaggedChunk = 4096 * kd, kShortestSplit = 2048 * kd;
         const int64_t per_round = cus / groups;
         if (p->valid_len) {
             P = (p->N + kRaggedChunk - 1) / kRaggedChunk;
@@ -102,9 +105,25 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
             if (rounds < 1) rounds = 1;
             P = per_round * rounds;
         } else {
-            P = (8 * cus + groups - 1) / groups;
-            const int64_t p_bal = (p->N + kBalancedChunk - 1) / kBalancedChunk;
-            if (P > p_bal) P = p_bal;
+            // more groups than compute units: as few chunks per sequence as fill the last round of
+            // workgroups to 90 % (each doubling of P costs 1-2 %, an uneven last round 3-4 %), and
+            // with one chunk per sequence the streaming kernel finishes the result itself
+            const int64_t p_fit = p->N / kShortestSplit;   // never split below kShortestSplit keys
+            const int64_t p_max = p_fit < 1 ? 1 : (p_fit > 8 ? 8 : p_fit);
+            double best = 0.0;
+            P = 1;
+            for (int64_t cand = 1; cand <= p_max; ++cand) {
+                const int64_t wgs = groups * cand;
+                const double fill = (double)wgs / (double)(((wgs + cus - 1) / cus) * cus);
+                if (fill >= 0.9) {
+                    P = cand;
+                    break;
+                }
+                if (fill > best) {
+                    best = fill;
+                    P = cand;
+                }
+            }
         }
     } else {
         constexpr int64_t kTargetChunk = 4096;

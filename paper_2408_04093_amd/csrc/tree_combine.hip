@@ -13,6 +13,8 @@
 // first batch fetched before anything else.  max and the sum of l are
 // log-depth wavefront reductions finished in LDS; the weights w_j are staged
 // in LDS once per 1024 partials.
+#include <type_traits>
+
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
@@ -42,23 +44,24 @@ __device__ __forceinline__ float block_reduce(float x, float *sh, bool is_max) {
     return r;
 }
 
-template <int D>
-__global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArgs a) {
-    constexpr float kLog2eF = 1.4426950408889634074f;
-    constexpr int kSlices = D / kSlice;
+// Where the partials of row bh = (b, token, head) live: [B,Hq,P] (chunked launch) or the
+// consecutive pieces of the row's segment, piece_rows apart (balanced launch).
+struct RowPartials {
+    int P;                 // number of partials
+    int64_t sm, so;        // strides between consecutive partials, in floats
+    const float *pm, *pl;  // first m and l
+    const float *po;       // first numerator row (column 0)
+};
 
-    const int tid = threadIdx.x;
-    const int c = tid & (kSlice - 1);
-    const int r = tid / kSlice;
-    const int64_t bh = blockIdx.x / kSlices;
-    const int col = (blockIdx.x % kSlices) * kSlice + c;
-    // where this row's partials live: [B,Hq,P] (chunked launch) or the consecutive pieces of the
-    // row's segment, piece_rows apart (balanced launch)
-    int P = a.P;
-    int64_t sm = 1, so = D;                      // strides between consecutive partials
-    const float *pm = a.part_m + bh * P;
-    const float *pl = a.part_l + bh * P;
-    const float *po = a.part_o + bh * P * D + col;
+template <int D>
+__device__ __forceinline__ RowPartials locate_row(const CombineArgs &a, int64_t bh) {
+    RowPartials rp;
+    rp.P = a.P;
+    rp.sm = 1;
+    rp.so = D;
+    rp.pm = a.part_m + bh * a.P;
+    rp.pl = a.part_l + bh * a.P;
+    rp.po = a.part_o + bh * a.P * D;
     if (a.cum) {
         const int b = (int)(bh / a.Hq), vrow = (int)(bh % a.Hq);
         const int t = vrow / a.heads, hq = vrow % a.heads;
@@ -71,19 +74,36 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
         const int64_t Lb = Lv - a.piece_cost;
         int64_t S = (a.cum[a.B] * G + a.W - 1) / a.W;
         S = S < a.min_share ? a.min_share : S;
-        P = 0;
+        rp.P = 0;
         if (Lv > 0) {
             const int64_t seg0 = a.cum[b] * G + j * Lv + a.piece_cost;   // first key, virtual position
             const int64_t w0 = seg0 / S, w1 = (seg0 + Lb - 1) / S;
             const int64_t id0 = w0 + (int64_t)b * G + j;
-            P = (int)(w1 - w0 + 1);
-            sm = a.piece_rows;
-            so = (int64_t)a.piece_rows * D;
-            pm = a.part_m + id0 * a.piece_rows + row;
-            pl = a.part_l + id0 * a.piece_rows + row;
-            po = a.part_o + (id0 * a.piece_rows + row) * D + col;
+            rp.P = (int)(w1 - w0 + 1);
+            rp.sm = a.piece_rows;
+            rp.so = (int64_t)a.piece_rows * D;
+            rp.pm = a.part_m + id0 * a.piece_rows + row;
+            rp.pl = a.part_l + id0 * a.piece_rows + row;
+            rp.po = a.part_o + (id0 * a.piece_rows + row) * D;
         }
     }
+    return rp;
+}
+
+template <int D>
+__global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArgs a) {
+    constexpr float kLog2eF = 1.4426950408889634074f;
+    constexpr int kSlices = D / kSlice;
+
+    const int tid = threadIdx.x;
+    const int c = tid & (kSlice - 1);
+    const int r = tid / kSlice;
+    const int64_t bh = blockIdx.x / kSlices;
+    const int col = (blockIdx.x % kSlices) * kSlice + c;
+    const RowPartials rp = locate_row<D>(a, bh);
+    const int P = rp.P;
+    const int64_t sm = rp.sm, so = rp.so;
+    const float *pm = rp.pm, *pl = rp.pl, *po = rp.po + col;
 
     __shared__ float sh_red[kWaves];
     __shared__ float sh_w[kTile];
@@ -138,7 +158,10 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
                 const int j = j0 + i * kGroups;
-                if (j < tn) acc = fmaf(sh_w[j], x[i], acc);
+                if (j < tn) {   // a partial without keys may hold anything: never multiplied
+                    const float wv = sh_w[j];
+                    acc = fmaf(wv, wv != 0.f ? x[i] : 0.f, acc);
+                }
             }
         }
     }
@@ -155,6 +178,84 @@ __global__ void __launch_bounds__(kThreads) tree_combine_kernel(const CombineArg
         else reinterpret_cast<float *>(a.out)[bh * D + col] = z;
     }
     if (tid == 0 && blockIdx.x % kSlices == 0) a.lse[bh] = mstar + logf(lstar);
+}
+
+// The same reduction with one wavefront per row, four rows per workgroup, for launches with
+// many rows (large batches, many query tokens): there the kernel above is bound by the rate at
+// which workgroups can be dispatched (one per row and 32-column slice: 69 us for 8192 rows).
+// Lane j holds the weight of partial j of the current batch of 64; the numerators are then
+// added partial by partial, each lane owning D / 64 adjacent columns, 16 loads in flight.
+template <int D>
+__global__ void __launch_bounds__(kThreads) tree_combine_rows_kernel(const CombineArgs a) {
+    constexpr float kLog2eF = 1.4426950408889634074f;
+    constexpr int kCols = D / kWave;   // columns per lane: 2 or 1
+    constexpr int kUnroll = 16;
+    typedef float colv __attribute__((ext_vector_type(kCols)));
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t bh = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (bh >= (int64_t)a.B * a.Hq) return;   // whole wavefront; the kernel has no workgroup barrier
+    const RowPartials rp = locate_row<D>(a, bh);
+    const int P = rp.P;
+
+    float mx = -__builtin_huge_valf();
+    for (int j = lane; j < P; j += kWave)
+        if (rp.pl[j * rp.sm] > 0.f) mx = fmaxf(mx, rp.pm[j * rp.sm]);
+    const float mstar = wave_max(mx);
+
+    colv acc;
+#pragma unroll
+    for (int k = 0; k < kCols; ++k) acc[k] = 0.f;
+    float lsum = 0.f;
+    if (mstar != -__builtin_huge_valf()) {
+        for (int j0 = 0; j0 < P; j0 += kWave) {
+            const int j = j0 + lane;
+            const float lj = j < P ? rp.pl[j * rp.sm] : 0.f;
+            const float wj = lj > 0.f ? exp2_hw((rp.pm[j * rp.sm] - mstar) * kLog2eF) : 0.f;
+            lsum = fmaf(wj, lj, lsum);
+            const int nb = P - j0 < kWave ? P - j0 : kWave;
+            // batches of 16 partials while that many are left, then batches of 4
+            auto batch = [&](auto unroll_c, int jj0) {
+                constexpr int U = decltype(unroll_c)::value;
+                colv x[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int jj = jj0 + u < nb ? jj0 + u : nb - 1;   // clamped: loads stay inside the row's partials
+                    x[u] = *reinterpret_cast<const colv *>(rp.po + (int64_t)(j0 + jj) * rp.so + kCols * lane);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int jj = jj0 + u;
+                    float wv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wj), jj & (kWave - 1)));
+                    if (jj >= nb) wv = 0.f;
+#pragma unroll
+                    for (int k = 0; k < kCols; ++k)   // a partial without keys may hold anything: never multiplied
+                        acc[k] = fmaf(wv, wv != 0.f ? x[u][k] : 0.f, acc[k]);
+                }
+            };
+            int jj0 = 0;
+            for (; jj0 + kUnroll <= nb; jj0 += kUnroll) batch(std::integral_constant<int, kUnroll>{}, jj0);
+            for (; jj0 < nb; jj0 += 4) batch(std::integral_constant<int, 4>{}, jj0);
+        }
+    }
+    float lstar = lsum;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) lstar += __shfl_xor(lstar, off);
+
+    // no key anywhere: out = 0, lse = -inf by definition
+    const bool empty = mstar == -__builtin_huge_valf();
+    colv z;
+#pragma unroll
+    for (int k = 0; k < kCols; ++k) z[k] = empty ? 0.f : acc[k] / lstar;
+    if (a.out_dtype == TA_BF16) {
+        unsigned short *o = reinterpret_cast<unsigned short *>(a.out) + bh * D + kCols * lane;
+        if constexpr (kCols == 2)
+            *reinterpret_cast<uint32_t *>(o) = (uint32_t)f32_to_bf16_rne(z[0]) | ((uint32_t)f32_to_bf16_rne(z[1]) << 16);
+        else
+            o[0] = f32_to_bf16_rne(z[0]);
+    } else {
+        *reinterpret_cast<colv *>(reinterpret_cast<float *>(a.out) + bh * D + kCols * lane) = z;
+    }
+    if (lane == 0) a.lse[bh] = empty ? mstar : mstar + logf(lstar);
 }
 
 // Energy pass: lse = m* + log(sum_j exp(m_j - m*) l_j) from the (m, l) partials alone
@@ -219,8 +320,28 @@ __global__ void __launch_bounds__(kThreads) sum_partials_kernel(const CombineArg
 
 }  // namespace
 
+// One wavefront per row pays from 512 rows on (4 us against 6 us; 4 against 17 at 2048 rows) as
+// long as a row has at most ~100 partials; a row of 256 partials takes it 1.5x as long as the
+// workgroup-per-slice kernel.  With the balanced layout the partials per row are not known here;
+// they are few except for a sequence much longer than the rest of its batch.
+#ifndef TA_COMBINE_ROWS_MIN
+#define TA_COMBINE_ROWS_MIN 512
+#endif
+constexpr int kRowKernelMaxP = 128;
+
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
-    const dim3 grid((uint32_t)((int64_t)a.B * a.Hq * (d / kSlice)));
+    const int64_t rows = (int64_t)a.B * a.Hq;
+    // the row kernel moves two adjacent columns per lane at d = 128: needs 8-byte aligned rows
+    const bool pairs_ok = d == 64 || (((reinterpret_cast<uintptr_t>(a.part_o) | reinterpret_cast<uintptr_t>(a.out)) &
+                                       (a.out_dtype == TA_BF16 ? 3u : 7u)) == 0 &&
+                                      (reinterpret_cast<uintptr_t>(a.part_o) & 7u) == 0);
+    if (rows >= TA_COMBINE_ROWS_MIN && pairs_ok && (a.cum != nullptr || a.P <= kRowKernelMaxP)) {
+        const dim3 grid((uint32_t)((rows + kWaves - 1) / kWaves));
+        if (d == 128) hipLaunchKernelGGL((tree_combine_rows_kernel<128>), grid, dim3(kThreads), 0, s, a);
+        else hipLaunchKernelGGL((tree_combine_rows_kernel<64>), grid, dim3(kThreads), 0, s, a);
+        return hipGetLastError();
+    }
+    const dim3 grid((uint32_t)(rows * (d / kSlice)));
     if (d == 128) hipLaunchKernelGGL((tree_combine_kernel<128>), grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL((tree_combine_kernel<64>), grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();

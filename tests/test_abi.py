@@ -77,9 +77,16 @@ def test_workspace_and_chunk_heuristic(lib):
     p.d = 96
     assert ta.ta_suggest_chunks(p) == 0 and ta.ta_workspace_bytes(p, 4) == 0
     p = llama_problem()
-    p.Sq = 8                # 8 tokens x group of 4 = 32 rows -> two token slices, partials for 8 x 32 heads
+    p.Sq = 8                # 8 tokens x group of 4 = 32 rows in one pass, partials for 8 x 32 heads
     assert ta.ta_workspace_bytes(p, 16) >= 8 * 32 * 16 * 130 * 4
-    assert (p.B * p.Hkv * 2 * ta.ta_suggest_chunks(p)) % 256 == 0
+    assert (p.B * p.Hkv * ta.ta_suggest_chunks(p)) % 256 == 0
+    # more (batch, kv head) groups than compute units: the fewest chunks that fill the last round
+    for B, N, want in [(64, 8192, 1), (48, 16384, 2), (48, 2048, 1), (256, 1024, 1)]:
+        p = llama_problem()
+        p.B, p.N = B, N
+        p.k_stride_h = p.v_stride_h = N * 128
+        p.k_stride_b = p.v_stride_b = 8 * N * 128
+        assert ta.ta_suggest_chunks(p) == want, (B, N)
 
 
 @pytest.mark.parametrize("mutate,code", [

@@ -275,6 +275,41 @@ def test_combine_alone_matches_oracle_on_given_partials():
                 assert abs(lse[b, h] - rl) <= 1e-5
 
 
+@pytest.mark.parametrize("rows,P,d", [(600, 1, 128), (515, 5, 128), (512, 40, 64), (700, 128, 128),
+                                      (513, 130, 128), (2050, 3, 64), (640, 70, 128)])
+def test_combine_many_rows_one_wavefront_per_row(rows, P, d):
+    """From 512 rows on ta_tree_combine reduces each row with one wavefront (up to 128 partials per
+    row; beyond that the workgroup-per-slice kernel again).  Partials without keys carry NaN numerators
+    that must never be touched; some rows have no keys at all."""
+    g = torch.Generator().manual_seed(900 + rows + P)
+    pm = (torch.randn((1, rows, P), generator=g) * 20).float()
+    pl = (torch.rand((1, rows, P), generator=g) * 50 + 0.5).float()
+    po = torch.randn((1, rows, P, d), generator=g).float() * pl[..., None]
+    dead = torch.rand((1, rows, P), generator=g) < 0.2
+    dead[0, 7] = True; dead[0, rows - 1] = True                       # rows with no keys at all
+    pm[dead] = -math.inf; pl[dead] = 0; po[dead] = float("nan")
+    out, lse = ta.tree_combine(pm.cuda(), pl.cuda(), po.cuda(), ta.TA_F32)
+    out_b, lse_b = ta.tree_combine(pm.cuda(), pl.cuda(), po.cuda(), ta.TA_BF16)
+    # the same partials at an address that is only 4-byte aligned: two-column accesses are not allowed
+    flat = torch.empty(po.numel() + 1, dtype=torch.float32, device="cuda")
+    flat[1:].copy_(po.flatten())
+    out_u, lse_u = ta.tree_combine(pm.cuda(), pl.cuda(), flat[1:].view(po.shape), ta.TA_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(lse, lse_b) and torch.equal(out.to(torch.bfloat16), out_b)
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    assert np.isfinite(out).all()
+    pmn, pln, pon = pm.numpy(), pl.numpy(), np.nan_to_num(po.numpy(), nan=0.0)
+    for h in list(range(0, rows, 37)) + [7, rows - 1]:
+        ro, rl = oracle.combine(pmn[0, h], pln[0, h], pon[0, h])
+        if rl == -math.inf:
+            assert not out[0, h].any() and lse[0, h] == -math.inf
+        else:
+            assert row_rel_l2(out[0, h], ro) <= 2e-6
+            assert abs(lse[0, h] - rl) <= 1e-5
+    assert row_rel_l2(out_u.cpu().numpy(), out.astype(np.float64)) <= 1e-6
+    assert lse_err(lse_u.cpu().numpy(), lse.astype(np.float64)) <= 2e-5     # one fp32 ulp at |lse| ~ 64 is 8e-6
+
+
 def test_d64_fp32_combine_and_bf16_rounding():
     g = torch.Generator().manual_seed(5)
     pm = torch.zeros((1, 1, 2)); pl = torch.ones((1, 1, 2))
@@ -735,6 +770,19 @@ def test_skewed_ragged_batch_is_balanced_over_the_device(d):
     w = W.make_qkv(5, 71, 1, d, 5000, torch.bfloat16, seed=87, device="cuda")       # multi-query, 71 heads
     w.valid_len = torch.tensor([5000, 17, 0, 2500, 1], dtype=torch.int32, device="cuda")
     check(w)
+
+
+def test_balanced_launch_with_many_rows_uses_the_row_combine():
+    """40 sequences x 16 heads = 640 rows through the balanced launch, one sequence far longer than
+    the rest (its rows have ~200 pieces), several empty."""
+    B, N = 40, 30000
+    w = W.make_qkv(B, 16, 4, 128, N, torch.bfloat16, seed=88, device="cuda")
+    g = torch.Generator().manual_seed(10)
+    vl = torch.randint(1, 400, (B,), generator=g, dtype=torch.int32)
+    vl[5] = N; vl[0] = 0; vl[39] = 0; vl[17] = 2500
+    w.valid_len = vl.cuda()
+    out, lse = check(w)
+    assert not out[0].any() and np.isneginf(lse[[0, 39]]).all()
 
 
 def test_ragged_batch_with_no_keys_at_all():
