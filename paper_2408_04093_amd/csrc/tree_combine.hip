@@ -259,11 +259,12 @@ __global__ void __launch_bounds__(kThreads) tree_combine_rows_kernel(const Combi
 }
 
 // Energy pass: lse = m* + log(sum_j exp(m_j - m*) l_j) from the (m, l) partials alone
-// (Algorithm 1 steps 4-6 as one reduction).  One wavefront per (b, h).
-__global__ void __launch_bounds__(kWave) energy_combine_kernel(const CombineArgs a) {
+// (Algorithm 1 steps 4-6 as one reduction).  One wavefront per (b, h), four per workgroup.
+__global__ void __launch_bounds__(kThreads) energy_combine_kernel(const CombineArgs a) {
     constexpr float kLog2eF = 1.4426950408889634074f;
-    const int lane = threadIdx.x;
-    const int64_t bh = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t bh = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (bh >= (int64_t)a.B * a.Hq) return;   // whole wavefront; the kernel has no workgroup barrier
     const float *pm = a.part_m + bh * a.P;
     const float *pl = a.part_l + bh * a.P;
     float mx = -__builtin_huge_valf();
@@ -348,7 +349,8 @@ hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
 }
 
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(energy_combine_kernel, dim3((uint32_t)((int64_t)a.B * a.Hq)), dim3(kWave), 0, s, a);
+    const int64_t rows = (int64_t)a.B * a.Hq;
+    hipLaunchKernelGGL(energy_combine_kernel, dim3((uint32_t)((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

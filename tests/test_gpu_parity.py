@@ -639,7 +639,8 @@ def test_graph_capture_and_replay():
 @pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("B,Sq,Hq,Hkv,N", [(1, 1, 4, 1, 1), (2, 1, 8, 2, 1000), (1, 1, 16, 1, 4099),
                                             (1, 3, 8, 2, 777), (2, 4, 32, 8, 5000), (1, 12, 8, 2, 600),
-                                            (1, 9, 16, 2, 450), (1, 1, 48, 1, 900), (2, 3, 40, 1, 350)])
+                                            (1, 9, 16, 2, 450), (1, 1, 48, 1, 900), (2, 3, 40, 1, 350), (1, 1, 3, 1, 700),
+                                            (1, 7, 6, 2, 3000)])
 def test_energy_and_two_pass_match_the_oracle(B, Sq, Hq, Hkv, N, d):
     if Sq == 1:
         w = W.make_qkv(B, Hq, Hkv, d, N, torch.bfloat16, seed=300 + N, device="cuda")
