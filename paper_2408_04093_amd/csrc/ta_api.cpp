@@ -148,10 +148,15 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
 // share of all keys (see decode_balanced_mfma_kernel).
 // It pays while there are at most a few (batch, kv head) groups per compute unit: with many short
 // sequences one workgroup per sequence (several resident per CU, their start-up latencies
-// overlapping) is faster than one workgroup walking through many pieces in turn.
+// overlapping) is faster than one workgroup walking through many pieces in turn.  Measured with
+// lengths uniform on [N/4, N]: 1024 groups of N = 4096 keys 217 us balanced against 243 us in
+// chunks, but 1024 groups of N = 1024 keys 66 us against 61 us; hence no balanced launch for
+// more groups than CUs when a sequence cannot exceed 4096 keys (at d = 128).
 inline bool use_balanced(const ta_problem *p) {
-    return p->valid_len != nullptr && use_mfma_path(p->qkv_dtype, p->d) && p->B <= balanced_max_batch() &&
-           launch_groups(p) <= 4 * (int64_t)device_compute_units();
+    if (p->valid_len == nullptr || !use_mfma_path(p->qkv_dtype, p->d) || p->B > balanced_max_batch()) return false;
+    const int64_t groups = launch_groups(p), cus = device_compute_units();
+    if (groups <= cus) return true;
+    return groups <= 4 * cus && p->N * p->d >= (int64_t)4096 * 128;
 }
 
 struct BalancedPlan {
