@@ -11,7 +11,7 @@
 // per KB streamed at g = 4 (dot2 + cross-lane reductions + per-head exp/FMA)
 // and twice that at g = 8 -- it measured ~80 % VALU-busy at g = 4 and
 // VALU-bound (3.9 TB/s) at g = 8.  QK^T and PV as 16x16x32 bf16 MFMAs with
-// the head dimension padded to the 16-row tile cost the same for any g <= 16
+// the heads padded to the 16-row tile cost the same for any g <= 16
 // and leave ~10 vector instructions per KB.
 //
 // Per wave and step: a tile of 32 keys (8 KB of K, 8 KB of V).
@@ -476,7 +476,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     };
 
     // One register tile of K and one of V per wave, refilled with the next step as soon as it has
-    // been consumed (two or three tiles in rotation measured no faster).  The steady-state loop is
+    // been consumed (a second V tile, requested a whole step ahead, measured no faster at 128k keys
+    // and 2.6 % slower at 1M: the stream is DRAM-bound, not latency-bound).  The steady-state loop is
     // entered with exactly the pattern of outstanding loads it leaves behind on every step (K tile,
     // then V tile), so the compiler's wait counts are exact: waiting for K leaves V in flight and
     // waiting for V leaves the next K in flight.
