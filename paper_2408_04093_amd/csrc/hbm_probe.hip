@@ -2,7 +2,8 @@
 //   1. streaming-read ceiling of the box: a read-only kernel over a buffer far
 //      larger than the last-level cache (128-bit loads, several in flight);
 //   2. a plain copy kernel of known size, the reference against which the
-//      rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled.
+//      rocprofv3 FETCH_SIZE / WRITE_SIZE counters are scaled;
+//   3. the launch floor: an empty kernel launched back to back.
 // usage: hbm_probe [MiB=2048] [iters=20]
 #include <hip/hip_runtime.h>
 #include <cstdint>
@@ -48,6 +49,11 @@ __global__ void __launch_bounds__(256) copy_plain(const v4i *__restrict__ src, v
     }
 }
 
+// launch floor: what two dependent launches cost when the kernels do nothing
+__global__ void empty_kernel(int *sink) {
+    if (sink == nullptr) __builtin_trap();
+}
+
 int main(int argc, char **argv) {
     const size_t mib = argc > 1 ? strtoull(argv[1], nullptr, 10) : 2048;
     const int iters = argc > 2 ? atoi(argv[2]) : 20;
@@ -89,6 +95,14 @@ int main(int argc, char **argv) {
         float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
         printf("copy_plain grid %5d: %8.1f us  %8.1f GB/s read+write (%zu B read, %zu B written per launch)\n",
                g, ms * 1e3 / iters, 2.0 * bytes / (ms * 1e-3 / iters) / 1e9, bytes, bytes);
+    }
+    for (int g : {1, 256}) {
+        for (int i = 0; i < 10; ++i) empty_kernel<<<g, 256>>>(sink);
+        CHECK(hipEventRecord(e0));
+        for (int i = 0; i < 200; ++i) empty_kernel<<<g, 256>>>(sink);
+        CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
+        float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+        printf("empty_kernel grid %5d: %8.2f us per launch (back to back on one stream)\n", g, ms * 1e3 / 200);
     }
     CHECK(hipDeviceSynchronize());
     CHECK(hipGetLastError());
