@@ -146,6 +146,20 @@ def test_ragged_problems_reserve_workspace_for_the_balanced_launch(lib):
     p.valid_len = FAKE
     # 256 shares + 16 x 8 segments, 4 rows of 130 floats each, plus the prefix table
     assert ta.ta_workspace_bytes(p, 1) >= (256 + 128) * 4 * 130 * 4 + 17 * 8 > plain
+    # many short sequences (more groups than compute units, capacity below 4096 keys): chunks, not shares
+    p = llama_problem()
+    p.B, p.N = 128, 1024
+    p.k_stride_h = p.v_stride_h = 1024 * 128
+    p.k_stride_b = p.v_stride_b = 8 * 1024 * 128
+    plain = ta.ta_workspace_bytes(p, 1)
+    p.valid_len = FAKE
+    assert ta.ta_workspace_bytes(p, 1) == plain and ta.ta_suggest_chunks(p) == 1
+    p.N = 8192                                   # long enough for the shares to pay: 1024 groups <= 4 per CU
+    p.k_stride_h = p.v_stride_h = 8192 * 128
+    p.k_stride_b = p.v_stride_b = 8 * 8192 * 128
+    assert ta.ta_workspace_bytes(p, 1) >= (256 + 1024) * 4 * 130 * 4
+    p.B = 129                                    # 1032 groups: beyond 4 per CU
+    assert ta.ta_workspace_bytes(p, 1) == 129 * 32 * 130 * 4
 
 
 def test_missing_library_fails_loudly(monkeypatch):
