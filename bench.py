@@ -254,7 +254,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "d64_256k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "d64_256k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16", "llama128k_sq32", "llama128k_sq64"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
                     help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "

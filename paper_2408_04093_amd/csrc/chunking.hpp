@@ -3,9 +3,13 @@
 // chunks handed to workgroups instead of devices.  Device code only.
 //
 // Launch order matters because the hardware dispatcher hands out workgroups
-// in index order: the index is chunk-major (all groups' chunk 0 first), so in
-// a ragged batch the empty chunks of short sequences sit at the end and leave
-// at once; with an explicit table of unequal chunks (P <= 256) the chunks are
+// in index order, workgroup i to XCD i mod 8: the index is chunk-major (all
+// groups' chunk 0 first), so in a ragged batch the empty chunks of short
+// sequences sit at the end and leave at once; inside one chunk index the row
+// slices (matrix-core kernel, more than 64 rows per kv head) are the slow
+// axis, so that with B * Hkv a multiple of 8 the workgroups that stream the
+// same chunk of K/V for different row slices start together on the same XCD
+// and share its L2 (two slices: 153 us against 179-195 us per launch); with an explicit table of unequal chunks (P <= 256) the chunks are
 // visited largest first (longest-processing-time order), which keeps a big
 // chunk from starting late and running alone at the end.
 #pragma once
@@ -39,7 +43,8 @@ __device__ __forceinline__ ChunkRange select_chunk(const PartialArgs &a, int *sh
     uint32_t id = blockIdx.x;
     const int rank = id / groups;
     id %= groups;
-    c.slice = id % (uint32_t)a.slices;  id /= (uint32_t)a.slices;
+    const uint32_t bh = (uint32_t)a.B * (uint32_t)a.Hkv;
+    c.slice = id / bh;  id %= bh;
     c.hk = id % (uint32_t)a.Hkv;
     c.b = id / (uint32_t)a.Hkv;
 
