@@ -9,7 +9,9 @@
 // slices (matrix-core kernel, more than 64 rows per kv head) are the slow
 // axis, so that with B * Hkv a multiple of 8 the workgroups that stream the
 // same chunk of K/V for different row slices start together on the same XCD
-// and share its L2 (two slices: 153 us against 179-195 us per launch); with an explicit table of unequal chunks (P <= 256) the chunks are
+// and share its L2 (two slices: 153 us against 179-195 us per launch; when
+// B * Hkv is not a multiple of 8 the launch index is padded to one, the
+// surplus workgroups exit at once); with an explicit table of unequal chunks (P <= 256) the chunks are
 // visited largest first (longest-processing-time order), which keeps a big
 // chunk from starting late and running alone at the end.
 #pragma once
@@ -18,6 +20,7 @@
 namespace ta {
 
 struct ChunkRange {
+    bool surplus;  // padding workgroup of the launch index: nothing to do
     int b, hk, slice, chunk;
     int64_t lo;   // first key of the chunk
     int64_t L;    // valid length of the sequence
@@ -39,14 +42,16 @@ template <int THREADS>
 __device__ __forceinline__ ChunkRange select_chunk(const PartialArgs &a, int *sh) {
     static_assert(THREADS >= kMaxRankedChunks, "one thread per ranked chunk");
     ChunkRange c;
-    const uint32_t groups = (uint32_t)a.B * (uint32_t)a.Hkv * (uint32_t)a.slices;
+    const uint32_t bh = (uint32_t)a.bh_launch;
+    const uint32_t groups = bh * (uint32_t)a.slices;
     uint32_t id = blockIdx.x;
     const int rank = id / groups;
     id %= groups;
-    const uint32_t bh = (uint32_t)a.B * (uint32_t)a.Hkv;
     c.slice = id / bh;  id %= bh;
     c.hk = id % (uint32_t)a.Hkv;
     c.b = id / (uint32_t)a.Hkv;
+    c.surplus = c.b >= a.B;
+    if (c.surplus) return c;   // the whole workgroup, before any barrier
 
     int64_t L = a.N;
     if (a.valid_len) {

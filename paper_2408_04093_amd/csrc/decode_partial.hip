@@ -154,6 +154,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    if (cr.surplus) return;
     const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
     const int hq0 = hk * a.g + cr.slice * GT;
     const int64_t lo = cr.lo;
@@ -315,7 +316,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
     constexpr int U = TA_U;
-    const int64_t blocks = (int64_t)a.B * a.Hkv * a.slices * a.P;
+    const int64_t blocks = launch_blocks(a);
     hipLaunchKernelGGL((decode_partial_kernel<D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -631,6 +631,7 @@ __global__ void __launch_bounds__(kThreads, TA_WPE(NRB)) decode_partial_mfma_ker
     __shared__ WaveStats st;
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    if (cr.surplus) return;
     const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
     process_range<D, MODE, NRB, false, SHARED ? 0 : TA_AUX>(a, rg, smem, st);
 }
@@ -754,7 +755,7 @@ hipError_t launch_mode(const PartialArgs &a, int mode, dim3 grid, hipStream_t s)
 
 template <int D>
 hipError_t launch_rows(const PartialArgs &a, int mode, hipStream_t s) {
-    const dim3 grid((uint32_t)((int64_t)a.B * a.Hkv * a.slices * a.P));
+    const dim3 grid((uint32_t)launch_blocks(a));
     const int rows = a.rows;
     if (rows <= 16) return launch_mode<D, 1>(a, mode, grid, s);
     if (rows <= 32) return launch_mode<D, 2>(a, mode, grid, s);

@@ -207,6 +207,8 @@ PartialArgs base_args(const ta_problem *p, const void *q, const void *K, const v
     a.Sq = tokens(p);
     a.rows = rows_per_slice(p);
     a.slices = (int32_t)(launch_groups(p) / ((int64_t)p->B * p->Hkv));
+    // several slices read the same K/V: aligned to the 8 XCDs so that they share an L2 (see select_chunk)
+    a.bh_launch = a.slices > 1 ? (p->B * p->Hkv + 7) / 8 * 8 : p->B * p->Hkv;
     a.c = (double)p->scale * kLog2e;
     return a;
 }
@@ -239,7 +241,7 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     a.out = direct_out; a.lse_out = direct_lse;
     a.P = P;
     a.t = (p->N + P - 1) / P;
-    if ((int64_t)a.B * a.Hkv * a.slices * (int64_t)P >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
+    if (launch_blocks(a) >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
     const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
                              ? launch_decode_partial_mfma(a, p->d, mode, static_cast<hipStream_t>(stream))
                              : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));

@@ -34,6 +34,8 @@ struct PartialArgs {
     int32_t B, Hq, Hkv, P;
     int32_t g;                  // Hq / Hkv
     int32_t slices;             // VALU kernel: g / heads-per-workgroup; MFMA kernel: row slices
+    int32_t bh_launch;          // (batch, kv head) pairs per slice in the launch index: B * Hkv, rounded up to a
+                                // multiple of 8 when there are several slices (the surplus workgroups exit at once)
     int32_t Sq;                 // query tokens per sequence (>= 1)
     int32_t rows;               // MFMA kernel: (token, head-in-group) rows per slice, <= 64.  Rows are numbered
                                 // token-major (row = token * g + head in group) and cut into slices of `rows`
@@ -65,6 +67,9 @@ inline int heads_per_workgroup(int dtype, int d, int g) {
     for (int gt : {8, 4, 2}) if (g % gt == 0) return gt;
     return 1;
 }
+
+// workgroups of a chunked launch
+inline int64_t launch_blocks(const PartialArgs &a) { return (int64_t)a.bh_launch * a.slices * a.P; }
 
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
 // resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
