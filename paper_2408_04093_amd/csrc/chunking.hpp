@@ -48,6 +48,9 @@ __device__ __forceinline__ ChunkRange select_chunk(const PartialArgs &a, int *sh
     const int rank = id / groups;
     id %= groups;
     c.slice = id / bh;  id %= bh;
+    // padded index (several slices): rotated by the chunk rank, or a batch with fewer than 8
+    // (batch, kv head) pairs would put all its work on the first XCDs
+    if (a.slices > 1) id = (id + bh - (uint32_t)rank % bh) % bh;
     c.hk = id % (uint32_t)a.Hkv;
     c.b = id / (uint32_t)a.Hkv;
     c.surplus = c.b >= a.B;
