@@ -11,6 +11,8 @@ input in the 256 MB last-level cache.  Prints ONE JSON line.
   roofline   the dominant kernel (decode_partial) alone: algorithmic bytes per
              launch / average launch time from events on the launch stream,
              against the 8 TB/s HBM3E peak
+             (roofline.stream_ceiling: what a read-only probe streams on this
+             very box, measured in the same run by a child process)
   cpu_baseline  the fp64 CPU oracle on the same bytes, in the same unit
 """
 import argparse
@@ -249,6 +251,27 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"
     return result
 
 
+def stream_ceiling():
+    """Read-only streaming rate of THIS box, measured now by the stand-alone probe (a child process):
+    the second denominator next to the published 8 TB/s.  None if the probe is not built."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2408_04093_amd", "hbm_probe")
+    if not os.path.exists(exe):
+        return None
+    try:
+        txt = subprocess.run([exe, "512", "10"], capture_output=True, text=True, timeout=120).stdout
+    except (OSError, subprocess.SubprocessError):
+        return None
+    rates = [float(x) for x in re.findall(r"read_only_nt grid\s+\d+:\s+[0-9.]+ us\s+([0-9.]+) GB/s", txt)]
+    floor = re.findall(r"empty_kernel grid\s+1:\s+([0-9.]+) us", txt)
+    if not rates:
+        return None
+    return {"value": max(rates), "unit": "GB/s",
+            "kind": "read-only kernel, non-temporal 128-bit loads, 512 MiB buffer (hbm_probe), best grid",
+            "empty_launch_us": float(floor[0]) if floor else None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -290,6 +313,12 @@ def main():
         m = run_workload("million", max(10, args.steps // 2), max(3, args.warmup // 4), False)
         result["also"] = {"million": {k: m[k] for k in ("value", "unit", "us_per_step", "pct_of_hbm_peak", "steps",
                                                          "config", "roofline")}}
+    if not args.no_extra:
+        torch.cuda.empty_cache()
+        sc = stream_ceiling()
+        if sc is not None:
+            sc["frac_of_it"] = round(result["roofline"]["achieved"] / sc["value"], 4)
+        result["roofline"]["stream_ceiling"] = sc
     print(json.dumps(result), flush=True)
 
 
