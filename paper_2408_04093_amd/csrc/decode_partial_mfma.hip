@@ -43,7 +43,6 @@ namespace ta {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -788,18 +787,5 @@ hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, hipStream_t 
 int balanced_max_batch() { return kMaxBalancedB; }
 int balanced_min_share(int d) { return kMinShareBytes / (2 * d); }
 int balanced_piece_cost(int d) { return kPieceCostBytes / (2 * d); }
-
-int decode_partial_mfma_occupancy() {
-    static const int cached = [] {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_partial_mfma_kernel<128, kFull, 1>, kThreads, 0) !=
-                hipSuccess || nb < 1) {
-            (void)hipGetLastError();
-            nb = 2;
-        }
-        return nb;
-    }();
-    return cached;
-}
 
 }  // namespace ta
