@@ -51,8 +51,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define TA_AUX 2   // non-temporal K/V loads (K/V are read once)
 #endif
 
+// Waves per SIMD the register budget is sized for.  With a 256-register budget (2 waves) the
+// compiler keeps MFMA results in vector registers; one and two row blocks fit it (165 and 242
+// registers; the balanced kernel, which also walks the share table, only with one).
 #ifndef TA_WPE
-#define TA_WPE(nrb) ((nrb) == 1 ? 2 : 1)   // waves per SIMD the register budget is sized for
+#define TA_WPE(nrb) ((nrb) <= 2 ? 2 : 1)
+#endif
+#ifndef TA_WPE_BALANCED
+#define TA_WPE_BALANCED(nrb) ((nrb) == 1 ? 2 : 1)
 #endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
@@ -390,8 +396,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 float ai[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) ai[i] = __shfl(alpha, (lane & 48) | (4 * r + i));
-                if constexpr (NRB == 1) {
-                    // the single-block kernels keep everything in vector registers: scale in place
+                if constexpr ((BALANCED ? TA_WPE_BALANCED(NRB) : TA_WPE(NRB)) == 2) {
+                    // kernels sized for 256 registers keep everything in vector registers: scale in place
 #pragma unroll
                     for (int j = 0; j < kCols; ++j)
 #pragma unroll
@@ -651,7 +657,7 @@ constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many b
 constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
 
 template <int D, int NRB>
-__global__ void __launch_bounds__(kThreads, TA_WPE(NRB)) decode_balanced_mfma_kernel(const PartialArgs a) {
+__global__ void __launch_bounds__(kThreads, TA_WPE_BALANCED(NRB)) decode_balanced_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ WaveStats st;
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
