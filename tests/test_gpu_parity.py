@@ -431,6 +431,41 @@ def test_scores_rising_along_the_sequence_move_the_shift_at_every_step(Sq, d):
             check(w, f32_out_tol=2e-4)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_problems_against_the_oracle(seed):
+    """Shapes drawn from a seeded generator: batch, tokens, group size (1..80, so up to several row
+    slices), kv heads, head dimension, length, ragged or not, sign and size of the scale."""
+    rng = np.random.default_rng(7000 + seed)
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 6))
+    Hkv = int(rng.integers(1, 4))
+    g = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 17, 33, 64, 80]))
+    Sq = int(rng.choice([1, 1, 1, 2, 3, 5, 9]))
+    if Sq * g > 400:
+        Sq = 1
+    N = int(rng.choice([1, 7, 31, 32, 33, 127, 128, 129, 500, 1024, 1500, 4097]))
+    scale = float(rng.choice([1.0, -0.7, 0.0, 0.25])) * d ** -0.5
+    if Sq > 1:
+        w = W.make_multi(B, Sq, g * Hkv, Hkv, d, N, torch.bfloat16, seed=7100 + seed, device="cuda", scale=scale)
+    else:
+        w = W.make_qkv(B, g * Hkv, Hkv, d, N, torch.bfloat16, seed=7100 + seed, device="cuda", scale=scale)
+    if rng.random() < 0.5:
+        w.valid_len = torch.from_numpy(rng.integers(0, N + 1, size=B).astype(np.int32)).cuda()
+    if Sq > 1:
+        check_multi(w)
+    else:
+        check(w)
+    # the two halves with an explicit chunk count as well
+    P = int(rng.choice([1, 2, 5, 13]))
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=P, valid_len=w.valid_len)
+    out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+    torch.cuda.synchronize()
+    vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
+    ref = (oracle.decode_causal if Sq > 1 else oracle.decode)(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
+    assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+
+
 # ------------------------------------------------------------------ full-size configs, bench launch shape
 def test_config1_llama_128k_full():
     w = W.llama128k(device="cuda")
