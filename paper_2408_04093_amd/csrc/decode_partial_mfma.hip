@@ -370,10 +370,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
         if constexpr (MODE != kGradient) {
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 16));
-#pragma unroll
             for (int rb = 0; rb < NRB; ++rb) {
-                mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 32));
+                mx[rb] = rows_max(mx[rb]);
                 m_true[rb] = fmaxf(m_true[rb], mx[rb]);
                 up[rb] = mx[rb] > m_run[rb] + kLazy;   // also true on a row's first keys (-inf + kLazy = -inf)
                 any_up |= up[rb];
@@ -525,8 +523,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         if (brows <= 0) break;
         // the row's normaliser is spread over the 4 row groups of the wave
         float lw = l_run[rb];
-        lw += __shfl_xor(lw, 16);
-        lw += __shfl_xor(lw, 32);
+        lw = rows_sum(lw);
         __syncthreads();
         if constexpr (MODE != kEnergy) {
 #pragma unroll

@@ -66,6 +66,25 @@ __device__ __forceinline__ float wave_max(float x) {
     return x;
 }
 
+// Maximum / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the same column position in the
+// four 16-lane rows of the wave), left in all four.  gfx950 swaps half-waves and 16-lane rows
+// between two registers in the vector ALU (v_permlane32_swap: upper half of the first with lower
+// half of the second; v_permlane16_swap: odd rows of the first with even rows of the second), so
+// with both operands holding x, one swap and one max / add fold each pair: no LDS round trip as
+// with ds_bpermute.
+__device__ __forceinline__ float rows_max(float x) {
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float m = fmaxf(__uint_as_float(h[0]), __uint_as_float(h[1]));
+    const auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+    return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float m = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+    const auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
 // 2^x on the hardware transcendental unit (v_exp_f32, about 1 ulp).
 __device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
 
