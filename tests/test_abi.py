@@ -138,6 +138,38 @@ def test_energy_and_two_pass_argument_checks(lib):
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
 
 
+def test_chunk_heuristic_invariants_on_seeded_random_problems(lib):
+    """For any valid problem: 1 <= P <= ceil(N / 256) (never chunks shorter than 256 keys), the
+    workspace covers the chunked layout, and the launch grid stays below 2^31 workgroups."""
+    import numpy as np
+    rng = np.random.default_rng(31)
+    for _ in range(400):
+        p = ta.Problem()
+        p.d = int(rng.choice([64, 128]))
+        p.Hkv = int(rng.choice([1, 2, 4, 8, 16]))
+        g = int(rng.choice([1, 2, 4, 7, 8, 16, 33, 71]))
+        p.Hq = p.Hkv * g
+        p.B = int(rng.choice([1, 2, 3, 5, 16, 48, 64, 300, 2049]))
+        p.N = int(rng.choice([1, 255, 256, 257, 1000, 4096, 5000, 65536, 1 << 20]))
+        bf16 = bool(rng.integers(0, 2))
+        p.qkv_dtype = ta.TA_BF16 if bf16 else ta.TA_F32
+        p.Sq = int(rng.choice([0, 1, 3, 17])) if bf16 else 0
+        if p.N * p.d * (2 if bf16 else 4) >= 1 << 32:
+            continue
+        p.k_stride_n = p.v_stride_n = p.d
+        p.k_stride_h = p.v_stride_h = p.N * p.d
+        p.k_stride_b = p.v_stride_b = p.Hkv * p.N * p.d
+        p.out_dtype, p.scale = ta.TA_F32, 0.1
+        p.valid_len = FAKE if rng.integers(0, 2) else None
+        P = ta.ta_suggest_chunks(p)
+        assert 1 <= P <= -(-p.N // 256), (p.B, p.Hq, p.Hkv, p.d, p.N, p.Sq, P)
+        sq = max(1, p.Sq)
+        assert ta.ta_workspace_bytes(p, P) >= p.B * sq * p.Hq * P * (p.d + 2) * 4
+        assert ta.ta_workspace_bytes(p, P) % 256 == 0
+        slices = -(-sq * g // 64) if bf16 else 1
+        assert p.B * p.Hkv * slices * P < 1 << 31
+
+
 def test_ragged_problems_reserve_workspace_for_the_balanced_launch(lib):
     p = llama_problem()
     p.B = 16
