@@ -653,7 +653,7 @@ constexpr int kMaxBalancedB = 2048;   // sequences whose prefix sums fit the LDS
 constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many bytes of K (512 keys at d = 128)
 constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
 
-template <int D, int NRB>
+template <int D, int MODE, int NRB>
 __global__ void __launch_bounds__(kThreads, TA_WPE_BALANCED(NRB)) decode_balanced_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ WaveStats st;
@@ -737,7 +737,7 @@ __global__ void __launch_bounds__(kThreads, TA_WPE_BALANCED(NRB)) decode_balance
                            (int64_t)blockIdx.x + (int64_t)b * G + j};
             if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
             first = false;
-            process_range<D, kFull, NRB, true>(a, rg, smem, st);
+            process_range<D, MODE, NRB, true>(a, rg, smem, st);
         }
         x += span;
     }
@@ -771,20 +771,21 @@ hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hip
     return hipErrorInvalidValue;
 }
 
-template <int D>
+template <int D, int MODE>
 hipError_t launch_balanced(const PartialArgs &a, hipStream_t s) {
     const dim3 grid((uint32_t)a.W);
     const int rows = a.rows;
-    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 1>), grid, dim3(kThreads), 0, s, a);
-    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 2>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, 4>), grid, dim3(kThreads), 0, s, a);
+    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 1>), grid, dim3(kThreads), 0, s, a);
+    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 2>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 4>), grid, dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, hipStream_t s) {
-    if (d == 128) return launch_balanced<128>(a, s);
-    if (d == 64) return launch_balanced<64>(a, s);
-    return hipErrorInvalidValue;
+hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hipStream_t s) {
+    if (d != 128 && d != 64) return hipErrorInvalidValue;
+    if (mode == kEnergy) return d == 128 ? launch_balanced<128, kEnergy>(a, s) : launch_balanced<64, kEnergy>(a, s);
+    if (mode != kFull) return hipErrorInvalidValue;   // the gradient pass has no balanced form
+    return d == 128 ? launch_balanced<128, kFull>(a, s) : launch_balanced<64, kFull>(a, s);
 }
 
 int balanced_max_batch() { return kMaxBalancedB; }

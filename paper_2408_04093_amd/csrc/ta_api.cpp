@@ -248,6 +248,34 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
+// Ragged batch on the balanced launch: equal shares of all keys per workgroup, then the combine over
+// each row's pieces.  mode 0 = (m,l,o) -> out and lse; mode 1 = energy pass (K only) -> lse.
+// The caller has checked the problem, the pointers and the workspace size.
+ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const void *V, void *workspace,
+                       int mode, void *out, float *lse, void *stream) {
+    const BalancedPlan bp = balanced_plan(p, device_compute_units());
+    char *base = static_cast<char *>(workspace);
+    PartialArgs a = base_args(p, q, K, V);
+    a.part_o = reinterpret_cast<float *>(base);
+    a.part_m = reinterpret_cast<float *>(base + bp.off_m);
+    a.part_l = reinterpret_cast<float *>(base + bp.off_l);
+    a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
+    a.W = bp.W;
+    a.piece_rows = bp.rows;
+    if (launch_decode_balanced_mfma(a, p->d, mode, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
+    CombineArgs c{};
+    c.part_m = a.part_m; c.part_l = a.part_l; c.part_o = a.part_o;
+    c.out = out; c.lse = lse;
+    c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = 0;
+    c.out_dtype = p->out_dtype;
+    c.cum = a.cum;
+    c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
+    c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.rows = a.rows;
+    const hipError_t e = mode == 1 ? launch_energy_combine(c, static_cast<hipStream_t>(stream))
+                                   : launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TA_OK : TA_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -313,28 +341,7 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
 
-    if (use_balanced(p)) {
-        // ragged batch: equal shares of all keys per workgroup, then the combine over each row's pieces
-        const BalancedPlan bp = balanced_plan(p, device_compute_units());
-        char *base = static_cast<char *>(workspace);
-        PartialArgs a = base_args(p, q, K, V);
-        a.part_o = reinterpret_cast<float *>(base);
-        a.part_m = reinterpret_cast<float *>(base + bp.off_m);
-        a.part_l = reinterpret_cast<float *>(base + bp.off_l);
-        a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
-        a.W = bp.W;
-        a.piece_rows = bp.rows;
-        if (launch_decode_balanced_mfma(a, p->d, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
-        CombineArgs c{};
-        c.part_m = a.part_m; c.part_l = a.part_l; c.part_o = a.part_o;
-        c.out = out; c.lse = lse;
-        c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = 0;
-        c.out_dtype = p->out_dtype;
-        c.cum = a.cum;
-        c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
-        c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.rows = a.rows;
-        return launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream)) == hipSuccess ? TA_OK : TA_ERR_HIP;
-    }
+    if (use_balanced(p)) return run_balanced(p, q, K, V, workspace, 0, out, lse, stream);
     if (P == 1 && use_mfma_path(p->qkv_dtype, p->d)) {
         // one chunk per sequence: the streaming kernel normalises and writes out / lse itself
         return run_partial(p, q, K, V, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 0, stream, out, lse);
@@ -360,6 +367,7 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
     if (!aligned16(q) || !aligned16(K)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
+    if (use_balanced(p)) return run_balanced(p, q, K, nullptr, workspace, 1, nullptr, lse, stream);
     if (P == 1)
         return run_partial(p, q, K, nullptr, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 1, stream, nullptr, lse);
     const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;

@@ -53,6 +53,7 @@ struct RowPartials {
     const float *po;       // first numerator row (column 0)
 };
 
+// D = 0: only m and l are located (energy pass: there are no numerators)
 template <int D>
 __device__ __forceinline__ RowPartials locate_row(const CombineArgs &a, int64_t bh) {
     RowPartials rp;
@@ -61,7 +62,7 @@ __device__ __forceinline__ RowPartials locate_row(const CombineArgs &a, int64_t 
     rp.so = D;
     rp.pm = a.part_m + bh * a.P;
     rp.pl = a.part_l + bh * a.P;
-    rp.po = a.part_o + bh * a.P * D;
+    rp.po = D ? a.part_o + bh * a.P * D : nullptr;
     if (a.cum) {
         const int b = (int)(bh / a.Hq), vrow = (int)(bh % a.Hq);
         const int t = vrow / a.heads, hq = vrow % a.heads;
@@ -84,7 +85,7 @@ __device__ __forceinline__ RowPartials locate_row(const CombineArgs &a, int64_t 
             rp.so = (int64_t)a.piece_rows * D;
             rp.pm = a.part_m + id0 * a.piece_rows + row;
             rp.pl = a.part_l + id0 * a.piece_rows + row;
-            rp.po = a.part_o + (id0 * a.piece_rows + row) * D;
+            rp.po = D ? a.part_o + (id0 * a.piece_rows + row) * D : nullptr;
         }
     }
     return rp;
@@ -265,20 +266,19 @@ __global__ void __launch_bounds__(kThreads) energy_combine_kernel(const CombineA
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t bh = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (bh >= (int64_t)a.B * a.Hq) return;   // whole wavefront; the kernel has no workgroup barrier
-    const float *pm = a.part_m + bh * a.P;
-    const float *pl = a.part_l + bh * a.P;
+    const RowPartials rp = locate_row<0>(a, bh);
     float mx = -__builtin_huge_valf();
-    for (int j = lane; j < a.P; j += kWave)
-        if (pl[j] > 0.f) mx = fmaxf(mx, pm[j]);
+    for (int j = lane; j < rp.P; j += kWave)
+        if (rp.pl[j * rp.sm] > 0.f) mx = fmaxf(mx, rp.pm[j * rp.sm]);
     mx = wave_max(mx);
     if (mx == -__builtin_huge_valf()) {
         if (lane == 0) a.lse[bh] = mx;
         return;
     }
     float ls = 0.f;
-    for (int j = lane; j < a.P; j += kWave) {
-        const float lj = pl[j];
-        if (lj > 0.f) ls = fmaf(exp2_hw((pm[j] - mx) * kLog2eF), lj, ls);
+    for (int j = lane; j < rp.P; j += kWave) {
+        const float lj = rp.pl[j * rp.sm];
+        if (lj > 0.f) ls = fmaf(exp2_hw((rp.pm[j * rp.sm] - mx) * kLog2eF), lj, ls);
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off);

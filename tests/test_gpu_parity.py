@@ -793,10 +793,17 @@ def test_skewed_ragged_batch_is_balanced_over_the_device(d):
         w.V[b, :, int(vl[b]):] = float("nan")
     out, lse = check(w)
     assert not out[0].any() and np.isneginf(lse[[0, 7, 23]]).all()
+    # the energy pass takes the same shares (K only) and must give the same lse
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    torch.cuda.synchronize()
+    assert lse_err(lse_e.cpu().numpy(), lse.astype(np.float64)) <= 1e-5
     # several query tokens through the same path (token slices become extra segments)
     wm = W.make_multi(6, 5, 16, 2, d, 9000, torch.bfloat16, seed=82, device="cuda")   # 5 x 8 = 40 rows
     wm.valid_len = torch.tensor([9000, 3, 0, 700, 5, 4321], dtype=torch.int32, device="cuda")
-    check_multi(wm)
+    _, ref_lse = check_multi(wm)
+    lse_e = ta.energy(wm.q, wm.K, wm.scale, wm.valid_len)
+    torch.cuda.synchronize()
+    assert lse_err(lse_e.cpu().numpy(), ref_lse) <= TOL_LSE
     wm = W.make_multi(3, 9, 16, 1, d, 2000, torch.bfloat16, seed=83, device="cuda")   # g = 16: 4 + 4 + 1 tokens
     wm.valid_len = torch.tensor([2000, 8, 1234], dtype=torch.int32, device="cuda")
     check_multi(wm)
