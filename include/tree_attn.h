@@ -171,8 +171,8 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
 
 /*
  * The energy alone: lse[b,(t,)h] = F(0) = logsumexp_a(scale q.k_a), Algorithm 1
- * ("Single Query Energy Forward") with the max and logsumexp reductions fused
- * into one (m, l) reduction.  zeta is zero and never materialised, so V is not
+ * (the energy forward pass for one query) with its max and logsumexp
+ * reductions fused into one (m, l) reduction.  zeta is zero and never materialised, so V is not
  * an argument and only K is streamed: half the bytes of ta_decode.  Ragged
  * batches take the same equal-cost shares as in ta_decode.
  *   workspace   as for ta_decode (same size and alignment)
