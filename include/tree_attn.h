@@ -34,7 +34,9 @@
  *     over the keys of one chunk, all fp32:  part_m, part_l [B,Hq,P] and
  *     part_o [B,Hq,P,d], contiguous.  The paper's per-device (o, lse) are
  *     o / l and m + log l.  An empty chunk stores (-inf, 0, 0).
- *   - NaN or Inf in q, K or V: behaviour undefined.
+ *   - NaN or Inf in q, K or V: behaviour undefined.  Sums are kept in fp32 with
+ *     weights of up to 2^8 while a chunk is streamed, so N * max|V| must stay
+ *     below ~1e35.
  *   - Several query tokens (Sq > 1; speculative decoding, the tail of a chunked
  *     prefill): the paper's causal energy F_tot = sum_i log sum_{a <= i} exp(..)
  *     (Appendix C.1) restricted to the last Sq positions.  The cache of
