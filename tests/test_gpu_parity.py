@@ -464,6 +464,12 @@ def test_seeded_random_problems_against_the_oracle(seed):
     ref = (oracle.decode_causal if Sq > 1 else oracle.decode)(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
     assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
     assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+    # Algorithm 1 alone and Algorithms 1 + 2 on the same problem
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    out2, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert lse_err(lse_e.cpu().numpy(), ref[1]) <= TOL_LSE and torch.equal(lse_e, lse2)
+    assert row_rel_l2(out2.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
 
 
 # ------------------------------------------------------------------ full-size configs, bench launch shape
