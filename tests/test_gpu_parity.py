@@ -621,6 +621,28 @@ def test_multi_token_more_tokens_than_keys_and_chunks_inside_the_new_tokens():
     assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
 
 
+def test_maximum_query_tokens_and_a_very_long_chunk_table():
+    """Sq = 4096 (the documented maximum): 64 row slices, causal among the new tokens; and
+    P = 100 000 chunks over 1000 keys: almost all of them empty."""
+    w = W.make_multi(1, 4096, 1, 1, 64, 5000, torch.bfloat16, seed=97, device="cuda")
+    ref_out, ref_lse = oracle.decode_causal(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale)
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    w.q = w.q[:, :4095]                       # 4097 tokens are refused, 4095 are not a multiple of anything
+    with pytest.raises(ta.TAError):
+        ta.decode(torch.cat([w.q, w.q[:, :2]], dim=1), w.K, w.V, w.scale)
+    w = W.make_qkv(1, 4, 1, 128, 1000, torch.bfloat16, seed=98, device="cuda")
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=100000)
+    assert int((pl > 0).sum().item()) == 4 * 1000          # one key per non-empty chunk
+    out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+    torch.cuda.synchronize()
+    ref = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+
+
 def test_multi_token_needs_bf16():
     w = W.make_multi(1, 2, 4, 1, 64, 100, torch.float32, seed=1, device="cuda")
     with pytest.raises(ta.TAError) as e:
