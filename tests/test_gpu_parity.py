@@ -864,6 +864,19 @@ def test_ragged_batch_with_no_keys_at_all():
     assert not out.any().item() and torch.isneginf(lse).all().item()
 
 
+def test_balanced_launch_with_a_thousand_sequences():
+    """1000 sequences of up to 4096 keys: about four (batch, kv head) groups per compute unit, the
+    most the balanced launch takes; every thread of a workgroup scans four lengths of the table."""
+    B = 1000
+    w = W.make_qkv(B, 2, 1, 128, 4096, torch.bfloat16, seed=89, device="cuda")
+    g = torch.Generator().manual_seed(11)
+    w.valid_len = torch.randint(0, 4097, (B,), generator=g, dtype=torch.int32).cuda()
+    w.valid_len[::97] = 0
+    p = ta.make_problem(w.q, w.K, w.V, w.scale, w.valid_len)
+    assert ta.ta_workspace_bytes(p, 1) > B * 2 * 130 * 4          # the balanced plan, not one chunk per sequence
+    check(w)
+
+
 def test_very_large_ragged_batch_falls_back_to_chunks():
     """More sequences than the balanced launch tabulates (2048): fixed-size chunks instead."""
     B = 2100
