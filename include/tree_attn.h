@@ -172,6 +172,27 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
                     void *out, float *lse, void *stream);
 
 /*
+ * ta_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, checks, kernels and results as
+ * ta_decode, but the workspace is a fixed 16 MiB array in device memory that
+ * the library's code object brings along (one copy per GPU, held until the
+ * process ends); this call allocates and frees nothing.
+ *   - A problem whose workspace would exceed 16 MiB
+ *     (ta_workspace_bytes(p, ta_suggest_chunks(p)) > 16 << 20) is refused with
+ *     TA_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in
+ *     time (different streams, different threads) race on it.  Calls on one
+ *     stream are ordered and safe; nothing in the array has to be cleared
+ *     between calls (every value a kernel reads was written by the same call).
+ *   - The array's device address is looked up on the first call on each
+ *     device (with the caller's current device); make that first call outside
+ *     graph capture.  TA_ERR_HIP if the lookup fails.
+ */
+ta_status ta_decode_noalloc(const ta_problem *p, const void *q, const void *K, const void *V,
+                            void *out, float *lse, void *stream);
+
+/*
  * The energy alone: lse[b,(t,)h] = F(0) = logsumexp_a(scale q.k_a), Algorithm 1
  * (the energy forward pass for one query) with its max and logsumexp
  * reductions fused into one (m, l) reduction.  zeta is zero and never materialised, so V is not

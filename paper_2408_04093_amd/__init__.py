@@ -7,6 +7,6 @@ fallback: if the library has not been built, loading raises.
 from ._ffi import (  # noqa: F401
     TA_BF16, TA_F32, TAError, Problem, lib_path, load,
     ta_status_string, ta_suggest_chunks, ta_workspace_bytes,
-    ta_decode_partial, ta_tree_combine, ta_decode, ta_energy, ta_decode_two_pass,
+    ta_decode_partial, ta_tree_combine, ta_decode, ta_decode_noalloc, ta_energy, ta_decode_two_pass,
     make_problem, decode, decode_partial, tree_combine, energy, decode_two_pass,
 )

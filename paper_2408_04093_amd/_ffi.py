@@ -62,6 +62,8 @@ def load():
     lib.ta_tree_combine.restype = ctypes.c_int
     lib.ta_decode.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.ta_decode.restype = ctypes.c_int
+    lib.ta_decode_noalloc.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+    lib.ta_decode_noalloc.restype = ctypes.c_int
     lib.ta_energy.argtypes = [pp, vp, vp, vp, ctypes.c_size_t, vp, vp]
     lib.ta_energy.restype = ctypes.c_int
     lib.ta_decode_two_pass.argtypes = [pp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
@@ -97,6 +99,10 @@ def ta_tree_combine(B, Hq, d, P, part_m, part_l, part_o, out, out_dtype, lse, st
 def ta_decode(problem, q, K, V, workspace, workspace_bytes, out, lse, stream):
     return int(load().ta_decode(ctypes.byref(problem), q, K, V, workspace, int(workspace_bytes),
                                 out, lse, stream or None))
+
+
+def ta_decode_noalloc(problem, q, K, V, out, lse, stream):
+    return int(load().ta_decode_noalloc(ctypes.byref(problem), q, K, V, out, lse, stream or None))
 
 
 def ta_energy(problem, q, K, workspace, workspace_bytes, lse, stream):

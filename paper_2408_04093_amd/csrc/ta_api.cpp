@@ -278,6 +278,29 @@ ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const 
 
 }  // namespace
 
+// ---- ta_decode for callers that cannot allocate: the workspace is a fixed array in device memory that
+// the library's code object brings along.  In host code the array's name is only a handle for the
+// runtime; the array's device address is looked up once per device (with that device current) and
+// that pointer is what is handed to the kernels.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+static ta_status scratch_of_current_device(void **ptr) {
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TA_ERR_HIP;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return TA_OK;
+}
+
 extern "C" {
 
 const char *ta_status_string(ta_status s) {
@@ -355,6 +378,19 @@ ta_status ta_decode(const ta_problem *p, const void *q, const void *K, const voi
     if (s2 != TA_OK) return s2;
     return ta_tree_combine(p->B, tokens(p) * p->Hq, p->d, P, part_m, part_l, part_o, out, p->out_dtype, lse,
                            stream);
+}
+
+ta_status ta_decode_noalloc(const ta_problem *p, const void *q, const void *K, const void *V,
+                            void *out, float *lse, void *stream) {
+    const ta_status st = check_problem(p);
+    if (st != TA_OK) return st;
+    if (!q || !K || !V || !out || !lse) return TA_ERR_NULL;
+    // the size check comes before the array is touched: too large a problem is refused on any machine
+    if (workspace_bytes(p, suggest_chunks(p, device_compute_units())) > kScratchBytes) return TA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const ta_status s1 = scratch_of_current_device(&ws);
+    if (s1 != TA_OK) return s1;
+    return ta_decode(p, q, K, V, ws, kScratchBytes, out, lse, stream);
 }
 
 ta_status ta_energy(const ta_problem *p, const void *q, const void *K,

@@ -44,7 +44,8 @@ def llama_problem():
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted([
         "ta_status_string", "ta_suggest_chunks", "ta_workspace_bytes",
-        "ta_decode_partial", "ta_tree_combine", "ta_decode", "ta_energy", "ta_decode_two_pass"])
+        "ta_decode_partial", "ta_tree_combine", "ta_decode", "ta_decode_noalloc", "ta_energy",
+        "ta_decode_two_pass"])
 
 
 def test_library_exports_every_declared_symbol(lib):
@@ -121,6 +122,18 @@ def test_null_alignment_and_workspace_errors(lib):
     assert ta.ta_tree_combine(1, 32, 96, 4, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == 6
     assert ta.ta_tree_combine(1, 32, 128, 0, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None) == 2
     assert ta.ta_tree_combine(1, 32, 128, 4, FAKE, FAKE, FAKE, FAKE, 5, FAKE, None) == 3
+
+
+def test_noalloc_entry_point_checks_and_size_limit(lib):
+    p = llama_problem()
+    assert ta.ta_decode_noalloc(p, None, FAKE, FAKE, FAKE, FAKE, None) == 1
+    p.d = 96
+    assert ta.ta_decode_noalloc(p, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 6
+    # partials beyond the library's 16 MiB device array: refused before the array is looked up
+    p = llama_problem()
+    p.Sq, p.N = 1024, 8192
+    assert ta.ta_workspace_bytes(p, ta.ta_suggest_chunks(p)) > 16 << 20
+    assert ta.ta_decode_noalloc(p, FAKE, FAKE, FAKE, FAKE, FAKE, None) == 5
 
 
 def test_energy_and_two_pass_argument_checks(lib):
