@@ -256,7 +256,7 @@ def stream_ceiling():
     the second denominator next to the published 8 TB/s.  None if the probe is not built."""
     import re
     import subprocess
-    exe = os.path.join(ROOT, "paper_2408_04093_amd", "hbm_probe")
+    exe = os.path.join(ROOT, "bench", "hbm_probe")
     if not os.path.exists(exe):
         return None
     try:

@@ -138,6 +138,14 @@ def make_problem(q, K, V, scale, valid_len=None, out_dtype=None):
         raise ValueError("q must be contiguous and K, V must have unit innermost stride")
     if K.shape != V.shape or K.shape[0] != B or K.shape[3] != d or not (q.dtype == K.dtype == V.dtype):
         raise ValueError("q, K, V shapes or dtypes disagree")
+    if valid_len is not None:
+        import torch
+        if valid_len.dtype != torch.int32 or tuple(valid_len.shape) != (B,) or not valid_len.is_contiguous():
+            raise ValueError("valid_len must be a contiguous int32 tensor of shape [B]")
+    if not (q.is_cuda and K.is_cuda and V.is_cuda) or not (q.device == K.device == V.device) or \
+            (valid_len is not None and valid_len.device != q.device):
+        raise ValueError("q, K, V (and valid_len) must be device tensors on one GPU: their addresses are "
+                         "dereferenced there")
     p = Problem()
     p.B, p.Hq, p.Hkv, p.d, p.N = B, Hq, Hkv, d, N
     p.k_stride_b, p.k_stride_h, p.k_stride_n = K.stride(0), K.stride(1), K.stride(2)

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtree_attn.so")
 SOURCES = ["ta_api.cpp", "decode_partial.hip", "decode_partial_mfma.hip", "tree_combine.hip"]
-HEADERS = ["ta_internal.hpp", "wave_ops.hpp", "chunking.hpp"]
+HEADERS = ["ta_internal.hpp", "wave_ops.hpp", "chunking.hpp", "mfma_tile.hpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -30,8 +30,8 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-PROBE_SRC = os.path.join(CSRC, "hbm_probe.hip")
-PROBE_BIN = os.path.join(HERE, "hbm_probe")
+PROBE_SRC = os.path.join(HERE, "..", "bench", "hbm_probe.hip")
+PROBE_BIN = os.path.join(HERE, "..", "bench", "hbm_probe")
 
 
 def build_probe(verbose: bool = False) -> str:

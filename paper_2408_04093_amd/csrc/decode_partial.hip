@@ -34,20 +34,11 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-// Tuning constants (overridable at compile time for sweeps)
-#ifndef TA_U
-#define TA_U 4          // keys per row group per pipeline step
-#endif
-#ifndef TA_AUX
-#define TA_AUX 2        // cache-policy bits of the K/V buffer loads: 2 = non-temporal.  K/V are
-                        // read once; streaming them non-temporally measured 7.0 TB/s against
-                        // 6.2 TB/s for default-policy loads on a read-only probe.
-#endif
-#ifndef TA_THREADS
-#define TA_THREADS 256
-#endif
-
-constexpr int kThreads = TA_THREADS;
+constexpr int kKeysPerStep = 4;   // keys per row group per pipeline step
+constexpr int kAux = 2;           // cache-policy bits of the K/V buffer loads: 2 = non-temporal.  K/V are
+                                  // read once; streaming them non-temporally measured 7.0 TB/s against
+                                  // 6.2 TB/s for default-policy loads on a read-only probe.
+constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 
 constexpr int kBytes = 4;   // fp32 K/V
@@ -205,10 +196,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
             const uint32_t vinc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, TA_AUX);
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, kAux);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, TA_AUX);
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, kAux);
         } else {
             // ragged last step: rows past the chunk are redirected to its last
             // row (always in range) and masked out of the arithmetic
@@ -220,10 +211,10 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, TA_AUX);
+                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, kAux);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, TA_AUX);
+                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, kAux);
         }
     };
 
@@ -315,10 +306,9 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
 template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
-    constexpr int U = TA_U;
+    constexpr int U = kKeysPerStep;
     const int64_t blocks = launch_blocks(a);
-    hipLaunchKernelGGL((decode_partial_kernel<D, GT, U>), dim3((uint32_t)blocks), dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    return launch_kernel(decode_partial_kernel<D, GT, U>, dim3((uint32_t)blocks), dim3(kThreads), s, a);
 }
 
 // resident workgroups per compute unit of one instantiation (register-bound)
@@ -326,7 +316,7 @@ template <int D, int GT>
 int occupancy_one() {
     static const int cached = [] {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, TA_U>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kKeysPerStep>, kThreads, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives

@@ -36,76 +36,23 @@
 #include <type_traits>
 
 #include "chunking.hpp"
+#include "mfma_tile.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
 namespace ta {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-#ifndef TA_AUX
-#define TA_AUX 2   // non-temporal K/V loads (K/V are read once)
-#endif
-
 // Waves per SIMD the register budget is sized for.  With a 256-register budget (2 waves) the
 // compiler keeps MFMA results in vector registers; one and two row blocks fit it (165 and 242
 // registers; the balanced kernel, which also walks the share table, only with one).
-#ifndef TA_WPE
-#define TA_WPE(nrb) ((nrb) <= 2 ? 2 : 1)
-#endif
-#ifndef TA_WPE_BALANCED
-#define TA_WPE_BALANCED(nrb) ((nrb) == 1 ? 2 : 1)
-#endif
+constexpr int waves_per_simd(int nrb, bool balanced) { return balanced ? (nrb == 1 ? 2 : 1) : (nrb <= 2 ? 2 : 1); }
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kTile = 32;                       // keys per wave step
 constexpr int kMaxHeads = 16;
 
-// Head-dimension geometry.  A K or V row (2 D bytes) is always spread over 16 lanes, so a lane
-// holds D / 16 consecutive columns of each of its 8 keys: 128-bit loads at d = 128, 64-bit at d = 64.
-template <int D>
-struct Geo {
-    static_assert(D == 128 || D == 64, "head dimension");
-    static constexpr int kCols = D / 16;            // columns per lane = PV tiles of 16 columns
-    static constexpr int kLaneBytes = 2 * kCols;    // bytes per lane per row
-    static constexpr int kWords = kCols / 2;        // dwords per lane per row
-    static constexpr int kSteps = D / 32;           // k-steps of the QK^T contraction
-    static constexpr int kPitch = 2 * D + 16;       // LDS bytes per staged K row (16-byte pad: conflict-free A reads)
-    static constexpr int kStage = kTile * kPitch;   // per wave
-    typedef int row_t __attribute__((ext_vector_type(kWords)));   // one lane's share of one row
-    // off: per-lane byte offset (a vector register); soff: wave-uniform byte offset (a scalar register)
-    // AUX: cache-policy bits of the load (2 = non-temporal, 0 = default)
-    template <int AUX>
-    static __device__ __forceinline__ row_t load(__amdgpu_buffer_rsrc_t rs, int off, int soff = 0) {
-        if constexpr (D == 128) return __builtin_amdgcn_raw_buffer_load_b128(rs, off, soff, AUX);
-        else return __builtin_amdgcn_raw_buffer_load_b64(rs, off, soff, AUX);
-    }
-};
-
-// tile row owned by (row group r, slot e): e = 4G + i  ->  16G + 4r + i
-__device__ __forceinline__ int kappa(int r, int e) { return 16 * (e >> 2) + 4 * r + (e & 3); }
-
-__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
-    bf16x2 p = {(__bf16)a, (__bf16)b};   // v_cvt_pk_bf16_f32, round to nearest even
-    uint32_t u;
-    __builtin_memcpy(&u, &p, 4);
-    return u;
-}
-
-// MODE selects what one pass computes (the paper's Algorithm 3 against its
-// Algorithms 1 and 2):
-//   kFull      (m, l, o) per chunk: Algorithm 3 steps 1-2.
-//   kEnergy    (m, l) only, K is the only stream: the energy / logsumexp pass of
-//              Algorithm 1 (zeta = 0 never materialised).
-//   kGradient  o = sum_a exp(s_a - lse) v_a with the final lse given: Algorithm 2
-//              step 5; no running max, no normaliser, partials add up plainly.
 // NRB is the number of 16-row blocks of (query token, head) pairs that share the
 // K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
-enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 
 // Per-wave row statistics handed through LDS when the waves of a workgroup are merged.
 struct WaveStats {
@@ -116,24 +63,9 @@ struct WaveStats {
     float fin[kMaxHeads];         // the merged row's final factor (partial) or normaliser (direct result)
 };
 
-// The running shift of a row is raised only when a step's row maximum exceeds it by more than
-// this many log2 units, so exponentials stay below 2^kLazy.  Raising on every new maximum is
-// not rare: with R rows riding on a wave, step t brings a new maximum for some row with
-// probability ~R/t, i.e. on most steps of a 4096-key chunk once 16 or more rows are live.
-constexpr float kLazy = 8.0f;
-
-// Where one range of keys of one (batch, kv head, token slice) goes.
-struct Range {
-    int b, hk, slice;
-    int64_t lo;     // first key
-    int n;          // number of keys
-    int64_t L;      // valid length of the sequence (causal limits among query tokens)
-    int64_t slot;   // chunked launch: chunk index; balanced launch: piece id
-};
-
 // The whole streaming computation for one range: called once per workgroup by the chunked kernel
 // and once per piece by the balanced kernel.  smem / st are the workgroup's LDS areas.
-template <int D, int MODE, int NRB, bool BALANCED, int AUX = TA_AUX>
+template <int D, int MODE, int NRB, bool BALANCED, int AUX = kAuxStream>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &rg, char *smem,
                                               WaveStats &st) {
     using G_ = Geo<D>;
@@ -394,7 +326,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 float ai[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) ai[i] = __shfl(alpha, (lane & 48) | (4 * r + i));
-                if constexpr ((BALANCED ? TA_WPE_BALANCED(NRB) : TA_WPE(NRB)) == 2) {
+                if constexpr (waves_per_simd(NRB, BALANCED) == 2) {
                     // kernels sized for 256 registers keep everything in vector registers: scale in place
 #pragma unroll
                     for (int j = 0; j < kCols; ++j)
@@ -628,14 +560,14 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 // instead of non-temporal ones, so that what one of them fetched stays in that XCD's L2 for the
 // others (64 query tokens at the llama shape: 256 us against 273 us per launch).
 template <int D, int MODE, int NRB, bool SHARED = false>
-__global__ void __launch_bounds__(kThreads, TA_WPE(NRB)) decode_partial_mfma_kernel(const PartialArgs a) {
+__global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, false)) decode_partial_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ WaveStats st;
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     if (cr.surplus) return;
     const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
-    process_range<D, MODE, NRB, false, SHARED ? 0 : TA_AUX>(a, rg, smem, st);
+    process_range<D, MODE, NRB, false, SHARED ? kAuxShared : kAuxStream>(a, rg, smem, st);
 }
 
 // Balanced launch for ragged batches (lengths known only on the device).  The keys of all
@@ -654,7 +586,7 @@ constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many b
 constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
 
 template <int D, int MODE, int NRB>
-__global__ void __launch_bounds__(kThreads, TA_WPE_BALANCED(NRB)) decode_balanced_mfma_kernel(const PartialArgs a) {
+__global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, true)) decode_balanced_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
     __shared__ WaveStats st;
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
@@ -748,11 +680,10 @@ __global__ void __launch_bounds__(kThreads, TA_WPE_BALANCED(NRB)) decode_balance
 template <int D, int NRB, bool SHARED = false>
 hipError_t launch_mode(const PartialArgs &a, int mode, dim3 grid, hipStream_t s) {
     switch (mode) {
-        case kEnergy: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kEnergy, NRB, SHARED>), grid, dim3(kThreads), 0, s, a); break;
-        case kGradient: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kGradient, NRB, SHARED>), grid, dim3(kThreads), 0, s, a); break;
-        default: hipLaunchKernelGGL((decode_partial_mfma_kernel<D, kFull, NRB, SHARED>), grid, dim3(kThreads), 0, s, a); break;
+        case kEnergy: return launch_kernel(decode_partial_mfma_kernel<D, kEnergy, NRB, SHARED>, grid, dim3(kThreads), s, a);
+        case kGradient: return launch_kernel(decode_partial_mfma_kernel<D, kGradient, NRB, SHARED>, grid, dim3(kThreads), s, a);
+        default: return launch_kernel(decode_partial_mfma_kernel<D, kFull, NRB, SHARED>, grid, dim3(kThreads), s, a);
     }
-    return hipGetLastError();
 }
 
 template <int D>
@@ -775,10 +706,9 @@ template <int D, int MODE>
 hipError_t launch_balanced(const PartialArgs &a, hipStream_t s) {
     const dim3 grid((uint32_t)a.W);
     const int rows = a.rows;
-    if (rows <= 16) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 1>), grid, dim3(kThreads), 0, s, a);
-    else if (rows <= 32) hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 2>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((decode_balanced_mfma_kernel<D, MODE, 4>), grid, dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    if (rows <= 16) return launch_kernel(decode_balanced_mfma_kernel<D, MODE, 1>, grid, dim3(kThreads), s, a);
+    if (rows <= 32) return launch_kernel(decode_balanced_mfma_kernel<D, MODE, 2>, grid, dim3(kThreads), s, a);
+    return launch_kernel(decode_balanced_mfma_kernel<D, MODE, 4>, grid, dim3(kThreads), s, a);
 }
 
 hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hipStream_t s) {

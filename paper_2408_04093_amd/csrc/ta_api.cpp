@@ -48,7 +48,9 @@ ta_status check_problem(const ta_problem *p) {
     }
     if (p->k_stride_n < p->d || p->v_stride_n < p->d) return TA_ERR_SHAPE;
     // 32-bit byte offsets inside one [N, d] head slice
+    // (divisions, so that absurd N or strides cannot overflow the product)
     const int64_t lim = (int64_t)1 << 32;
+    if (p->N >= lim / (p->k_stride_n * eb) + 1 || p->N >= lim / (p->v_stride_n * eb) + 1) return TA_ERR_UNSUPPORTED;
     if (p->N * p->k_stride_n * eb >= lim || p->N * p->v_stride_n * eb >= lim) return TA_ERR_UNSUPPORTED;
     if (p->Sq < 0 || p->Sq > 4096) return TA_ERR_SHAPE;
     if (p->Sq > 1 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;

@@ -53,6 +53,14 @@ struct CombineArgs {
     int32_t W, min_share, piece_cost, piece_rows;
     int32_t heads, g, Hkv, slices, rows; // real Hq, group size, kv heads, row slices, rows per slice
 };
+// Launch a kernel that takes one descriptor struct by value and return THIS launch's status (not
+// the runtime's sticky last-error state, which an unrelated earlier call may have set).
+template <typename Args>
+inline hipError_t launch_kernel(void (*kernel)(Args), dim3 grid, dim3 block, hipStream_t s, const Args &a) {
+    void *params[] = {const_cast<Args *>(&a)};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, params, 0, s);
+}
+
 // energy pass: lse from (m, l) partials only; gradient pass: out = plain sum of the partial numerators
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s);
 hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s);

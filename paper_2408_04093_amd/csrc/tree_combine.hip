@@ -325,9 +325,7 @@ __global__ void __launch_bounds__(kThreads) sum_partials_kernel(const CombineArg
 // long as a row has at most ~100 partials; a row of 256 partials takes it 1.5x as long as the
 // workgroup-per-slice kernel.  With the balanced layout the partials per row are not known here;
 // they are few except for a sequence much longer than the rest of its batch.
-#ifndef TA_COMBINE_ROWS_MIN
-#define TA_COMBINE_ROWS_MIN 512
-#endif
+constexpr int kRowKernelMinRows = 512;
 constexpr int kRowKernelMaxP = 128;
 
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
@@ -336,29 +334,25 @@ hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s) {
     const bool pairs_ok = d == 64 || (((reinterpret_cast<uintptr_t>(a.part_o) | reinterpret_cast<uintptr_t>(a.out)) &
                                        (a.out_dtype == TA_BF16 ? 3u : 7u)) == 0 &&
                                       (reinterpret_cast<uintptr_t>(a.part_o) & 7u) == 0);
-    if (rows >= TA_COMBINE_ROWS_MIN && pairs_ok && (a.cum != nullptr || a.P <= kRowKernelMaxP)) {
+    if (rows >= kRowKernelMinRows && pairs_ok && (a.cum != nullptr || a.P <= kRowKernelMaxP)) {
         const dim3 grid((uint32_t)((rows + kWaves - 1) / kWaves));
-        if (d == 128) hipLaunchKernelGGL((tree_combine_rows_kernel<128>), grid, dim3(kThreads), 0, s, a);
-        else hipLaunchKernelGGL((tree_combine_rows_kernel<64>), grid, dim3(kThreads), 0, s, a);
-        return hipGetLastError();
+        if (d == 128) return launch_kernel(tree_combine_rows_kernel<128>, grid, dim3(kThreads), s, a);
+        return launch_kernel(tree_combine_rows_kernel<64>, grid, dim3(kThreads), s, a);
     }
     const dim3 grid((uint32_t)(rows * (d / kSlice)));
-    if (d == 128) hipLaunchKernelGGL((tree_combine_kernel<128>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((tree_combine_kernel<64>), grid, dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    if (d == 128) return launch_kernel(tree_combine_kernel<128>, grid, dim3(kThreads), s, a);
+    return launch_kernel(tree_combine_kernel<64>, grid, dim3(kThreads), s, a);
 }
 
 hipError_t launch_energy_combine(const CombineArgs &a, hipStream_t s) {
     const int64_t rows = (int64_t)a.B * a.Hq;
-    hipLaunchKernelGGL(energy_combine_kernel, dim3((uint32_t)((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    return launch_kernel(energy_combine_kernel, dim3((uint32_t)((rows + kWaves - 1) / kWaves)), dim3(kThreads), s, a);
 }
 
 hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s) {
     const dim3 grid((uint32_t)((int64_t)a.B * a.Hq * (d / kSlice)));
-    if (d == 128) hipLaunchKernelGGL((sum_partials_kernel<128>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((sum_partials_kernel<64>), grid, dim3(kThreads), 0, s, a);
-    return hipGetLastError();
+    if (d == 128) return launch_kernel(sum_partials_kernel<128>, grid, dim3(kThreads), s, a);
+    return launch_kernel(sum_partials_kernel<64>, grid, dim3(kThreads), s, a);
 }
 
 }  // namespace ta

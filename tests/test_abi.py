@@ -207,6 +207,28 @@ def test_ragged_problems_reserve_workspace_for_the_balanced_launch(lib):
     assert ta.ta_workspace_bytes(p, 1) == 129 * 32 * 130 * 4
 
 
+def test_binding_refuses_host_tensors_and_wrong_length_tables():
+    import torch
+    q = torch.zeros((2, 8, 64), dtype=torch.bfloat16)
+    K = torch.zeros((2, 2, 16, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="int32"):
+        ta.make_problem(q, K, K, 1.0, torch.tensor([3, 4]))                      # int64 lengths
+    with pytest.raises(ValueError, match="int32"):
+        ta.make_problem(q, K, K, 1.0, torch.tensor([3, 4, 5], dtype=torch.int32))   # wrong shape
+    with pytest.raises(ValueError, match="device tensors"):
+        ta.make_problem(q, K, K, 1.0, torch.tensor([3, 4], dtype=torch.int32))   # host memory
+    with pytest.raises(ValueError, match="disagree"):
+        ta.make_problem(q, K.float(), K.float(), 1.0)
+
+
+def test_size_check_does_not_overflow(lib):
+    p = llama_problem()
+    p.N = (1 << 62)
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
+    p.N, p.k_stride_n = 1 << 20, 1 << 45
+    assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     from paper_2408_04093_amd import _ffi
     monkeypatch.setattr(_ffi, "_lib", None)
