@@ -212,7 +212,8 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
  * With lse known no running max and no normaliser are needed and the chunk
  * partials add up plainly.  K is streamed twice (1.5 x the bytes of ta_decode);
  * it exists as an on-GPU cross-check of Observation 1 and for callers that
- * already hold lse.  Arguments as for ta_decode.  bf16 only.
+ * already hold lse.  Arguments as for ta_decode.  A ragged batch takes the
+ * equal-cost shares of ta_decode in both passes.  bf16 only.
  */
 ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
                              void *workspace, size_t workspace_bytes,

@@ -19,10 +19,13 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB) or \
+    path = _build.LIB
+    if os.environ.get("TA_ORACLE_SANITIZED") == "1":   # the sanitizer run of the pins (tests/test_sanitized_oracle.py)
+        path = _build.SAN_LIB
+    elif not os.path.exists(_build.LIB) or \
             os.path.getmtime(_build.LIB) < os.path.getmtime(_build.SRC):
         _build.build()
-    lib = ctypes.CDLL(_build.LIB)
+    lib = ctypes.CDLL(path)
     c_int, c_i64, c_dbl, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
     lib.ta_oracle_decode.argtypes = [c_int, c_int, c_int, c_int, c_i64, vp, vp, vp, c_int,
                                      c_dbl, vp, vp, vp, c_int]

@@ -35,6 +35,7 @@
 // (kappa below) applied to P and V alike.
 #include <type_traits>
 
+#include "balanced_index.hpp"
 #include "chunking.hpp"
 #include "mfma_tile.hpp"
 #include "ta_internal.hpp"
@@ -600,7 +601,7 @@ __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, true)) decode_ba
             L = a.valid_len[bb];
             L = L < 0 ? 0 : (L > a.N ? a.N : L);
         }
-        return L > 0 ? L + kPieceCost : 0;
+        return balanced::virtual_len(L, kPieceCost);
     };
     // exclusive prefix sums of the virtual lengths: each thread takes a run of sequences, then a
     // 256-wide scan of the run totals
@@ -638,41 +639,15 @@ __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, true)) decode_ba
     if (blockIdx.x == 0)   // the combine kernel reads the same table
         for (int i = tid; i <= a.B; i += kThreads) a.cum[i] = sh_cum[i];
 
+    // this workgroup's share of all (virtual) keys, piece by piece (balanced_index.hpp)
     const int64_t G = (int64_t)a.Hkv * a.slices;
-    const int64_t T = sh_cum[a.B] * G;
-    int64_t S = (T + a.W - 1) / a.W;
-    S = S < kMinShare ? kMinShare : S;
-    const int64_t x0 = (int64_t)blockIdx.x * S;
-    const int64_t x1 = x0 + S < T ? x0 + S : T;
-    if (x0 >= T) return;
-
-    int b = 0, hi_b = a.B;   // cum[b] * G <= x0 < cum[hi_b] * G
-    while (hi_b - b > 1) {
-        const int mid = (b + hi_b) >> 1;
-        if (sh_cum[mid] * G <= x0) b = mid; else hi_b = mid;
-    }
     bool first = true;
-    for (int64_t x = x0; x < x1;) {
-        while (sh_cum[b + 1] * G <= x) ++b;        // also skips empty sequences; b < B because x < T
-        const int64_t Lv = sh_cum[b + 1] - sh_cum[b];   // virtual length of this sequence's segments
-        const int64_t Lb = Lv - kPieceCost;             // its keys
-        const int64_t rel = x - sh_cum[b] * G;
-        const int64_t j = rel / Lv;                // (kv head, token slice) of this sequence
-        const int64_t v0 = rel - j * Lv;           // virtual offset inside the segment
-        const int64_t span = (Lv - v0) < (x1 - x) ? (Lv - v0) : (x1 - x);
-        // the first kPieceCost virtual keys of a segment are the charge, the rest are its keys
-        const int64_t k0 = v0 > kPieceCost ? v0 - kPieceCost : 0;
-        int64_t k1 = v0 + span - kPieceCost;
-        k1 = k1 > Lb ? Lb : k1;
-        if (k1 > k0) {
-            const Range rg{b, (int)(j / a.slices), (int)(j % a.slices), k0, (int)(k1 - k0), Lb,
-                           (int64_t)blockIdx.x + (int64_t)b * G + j};
-            if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
-            first = false;
-            process_range<D, MODE, NRB, true>(a, rg, smem, st);
-        }
-        x += span;
-    }
+    balanced::for_each_piece(sh_cum, a.B, G, a.W, kMinShare, kPieceCost, (int)blockIdx.x, [&](const balanced::Piece &pc) {
+        const Range rg{pc.b, (int)(pc.j / a.slices), (int)(pc.j % a.slices), pc.k0, pc.n, pc.L, pc.id};
+        if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
+        first = false;
+        process_range<D, MODE, NRB, true>(a, rg, smem, st);
+    });
 }
 
 }  // namespace
@@ -713,9 +688,12 @@ hipError_t launch_balanced(const PartialArgs &a, hipStream_t s) {
 
 hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hipStream_t s) {
     if (d != 128 && d != 64) return hipErrorInvalidValue;
-    if (mode == kEnergy) return d == 128 ? launch_balanced<128, kEnergy>(a, s) : launch_balanced<64, kEnergy>(a, s);
-    if (mode != kFull) return hipErrorInvalidValue;   // the gradient pass has no balanced form
-    return d == 128 ? launch_balanced<128, kFull>(a, s) : launch_balanced<64, kFull>(a, s);
+    switch (mode) {
+        case kFull: return d == 128 ? launch_balanced<128, kFull>(a, s) : launch_balanced<64, kFull>(a, s);
+        case kEnergy: return d == 128 ? launch_balanced<128, kEnergy>(a, s) : launch_balanced<64, kEnergy>(a, s);
+        case kGradient: return d == 128 ? launch_balanced<128, kGradient>(a, s) : launch_balanced<64, kGradient>(a, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 int balanced_max_batch() { return kMaxBalancedB; }

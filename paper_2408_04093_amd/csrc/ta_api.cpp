@@ -251,7 +251,8 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
 }
 
 // Ragged batch on the balanced launch: equal shares of all keys per workgroup, then the combine over
-// each row's pieces.  mode 0 = (m,l,o) -> out and lse; mode 1 = energy pass (K only) -> lse.
+// each row's pieces.  mode 0 = (m,l,o) -> out and lse; mode 1 = energy pass (K only) -> lse;
+// mode 2 = gradient pass given lse -> out (plain sum of the pieces' numerators).
 // The caller has checked the problem, the pointers and the workspace size.
 ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const void *V, void *workspace,
                        int mode, void *out, float *lse, void *stream) {
@@ -262,6 +263,7 @@ ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const 
     a.part_m = reinterpret_cast<float *>(base + bp.off_m);
     a.part_l = reinterpret_cast<float *>(base + bp.off_l);
     a.cum = reinterpret_cast<int64_t *>(base + bp.off_cum);
+    a.lse_in = mode == 2 ? lse : nullptr;
     a.W = bp.W;
     a.piece_rows = bp.rows;
     if (launch_decode_balanced_mfma(a, p->d, mode, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
@@ -273,8 +275,9 @@ ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const 
     c.cum = a.cum;
     c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
     c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.rows = a.rows;
-    const hipError_t e = mode == 1 ? launch_energy_combine(c, static_cast<hipStream_t>(stream))
-                                   : launch_tree_combine(c, p->d, static_cast<hipStream_t>(stream));
+    const hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = mode == 1 ? launch_energy_combine(c, s)
+                         : mode == 2 ? launch_sum_partials(c, p->d, s) : launch_tree_combine(c, p->d, s);
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
@@ -430,6 +433,8 @@ ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, 
     if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !out_aligned(out, p->out_dtype)) return TA_ERR_ALIGN;
     const ta_status s1 = ta_energy(p, q, K, workspace, workspace_bytes_given, lse, stream);
     if (s1 != TA_OK) return s1;
+    // a ragged batch takes equal-cost shares in both passes
+    if (use_balanced(p)) return run_balanced(p, q, K, V, workspace, 2, out, lse, stream);
     const int32_t P = suggest_chunks(p, device_compute_units());
     float *part_o = static_cast<float *>(workspace);
     const ta_status s2 = run_partial(p, q, K, V, P, nullptr, nullptr, nullptr, part_o, lse, 2, stream);

@@ -84,7 +84,7 @@ hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStre
 int decode_partial_occupancy(int dtype, int d, int gt);
 // bf16, d in {64, 128}.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)
 hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hipStream_t s);
-// mode: 0 = (m,l,o), 1 = energy pass
+// mode: 0 = (m,l,o), 1 = energy pass, 2 = gradient pass
 hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hipStream_t s);
 int balanced_max_batch();
 int balanced_min_share(int d);     // virtual keys

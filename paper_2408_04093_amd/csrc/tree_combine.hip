@@ -15,6 +15,7 @@
 // in LDS once per 1024 partials.
 #include <type_traits>
 
+#include "balanced_index.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
 
@@ -69,23 +70,16 @@ __device__ __forceinline__ RowPartials locate_row(const CombineArgs &a, int64_t 
         const int grow = t * a.g + hq % a.g;            // row number inside the kv head, token-major
         const int row = grow % a.rows;
         const int64_t G = (int64_t)a.Hkv * a.slices;
-        const int64_t j = (int64_t)(hq / a.g) * a.slices + grow / a.rows;
-        // cum holds virtual lengths: keys + piece_cost per non-empty segment, the keys coming last
-        const int64_t Lv = a.cum[b + 1] - a.cum[b];
-        const int64_t Lb = Lv - a.piece_cost;
-        int64_t S = (a.cum[a.B] * G + a.W - 1) / a.W;
-        S = S < a.min_share ? a.min_share : S;
-        rp.P = 0;
-        if (Lv > 0) {
-            const int64_t seg0 = a.cum[b] * G + j * Lv + a.piece_cost;   // first key, virtual position
-            const int64_t w0 = seg0 / S, w1 = (seg0 + Lb - 1) / S;
-            const int64_t id0 = w0 + (int64_t)b * G + j;
-            rp.P = (int)(w1 - w0 + 1);
+        const int64_t j = (int64_t)(hq / a.g) * a.slices + grow / a.rows;   // segment of the sequence
+        const balanced::SegmentPieces sp =
+            balanced::pieces_of_segment(a.cum, a.B, G, a.W, a.min_share, a.piece_cost, b, j);
+        rp.P = sp.count;
+        if (sp.count > 0) {
             rp.sm = a.piece_rows;
             rp.so = (int64_t)a.piece_rows * D;
-            rp.pm = a.part_m + id0 * a.piece_rows + row;
-            rp.pl = a.part_l + id0 * a.piece_rows + row;
-            rp.po = D ? a.part_o + (id0 * a.piece_rows + row) * D : nullptr;
+            rp.pm = a.part_m + sp.id0 * a.piece_rows + row;
+            rp.pl = a.part_l + sp.id0 * a.piece_rows + row;
+            rp.po = D ? a.part_o + (sp.id0 * a.piece_rows + row) * D : nullptr;
         }
     }
     return rp;
@@ -286,6 +280,7 @@ __global__ void __launch_bounds__(kThreads) energy_combine_kernel(const CombineA
 }
 
 // Gradient pass (Algorithm 2 step 6): out = Reduce(sum) of the per-chunk numerators, no weights.
+// The numerators of a row are its P chunks or, after a balanced launch, the pieces of its segment.
 template <int D>
 __global__ void __launch_bounds__(kThreads) sum_partials_kernel(const CombineArgs a) {
     constexpr int kSlices = D / kSlice;
@@ -294,16 +289,17 @@ __global__ void __launch_bounds__(kThreads) sum_partials_kernel(const CombineArg
     const int r = tid / kSlice;
     const int64_t bh = blockIdx.x / kSlices;
     const int col = (blockIdx.x % kSlices) * kSlice + c;
-    const float *po = a.part_o + bh * a.P * D + col;
+    const RowPartials rp = locate_row<D>(a, bh);
+    const float *po = rp.po + col;
     __shared__ float sh_o[kGroups][kSlice];
 
     float acc = 0.f;
-    for (int j0 = r; j0 < a.P; j0 += kGroups * kBatch) {
+    for (int j0 = r; j0 < rp.P; j0 += kGroups * kBatch) {
         float x[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
             const int j = j0 + i * kGroups;
-            x[i] = j < a.P ? po[(int64_t)j * D] : 0.f;
+            x[i] = j < rp.P ? po[(int64_t)j * rp.so] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) acc += x[i];

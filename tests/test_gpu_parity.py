@@ -825,6 +825,12 @@ def test_skewed_ragged_batch_is_balanced_over_the_device(d):
     lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
     torch.cuda.synchronize()
     assert lse_err(lse_e.cpu().numpy(), lse.astype(np.float64)) <= 1e-5
+    # Algorithms 1 + 2 on the same shares: the gradient pass sums the pieces' numerators plainly
+    out2, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert row_rel_l2(out2.cpu().numpy(), out.astype(np.float64)) <= 2e-5
+    assert lse_err(lse2.cpu().numpy(), lse.astype(np.float64)) <= 1e-5
+    assert not out2[0].any() and not out2[7].any()
     # several query tokens through the same path (token slices become extra segments)
     wm = W.make_multi(6, 5, 16, 2, d, 9000, torch.bfloat16, seed=82, device="cuda")   # 5 x 8 = 40 rows
     wm.valid_len = torch.tensor([9000, 3, 0, 700, 5, 4321], dtype=torch.int32, device="cuda")
@@ -837,7 +843,10 @@ def test_skewed_ragged_batch_is_balanced_over_the_device(d):
     check_multi(wm)
     wm = W.make_multi(4, 3, 48, 2, d, 3000, torch.bfloat16, seed=86, device="cuda")   # g = 24: 72 rows, 64 + 8
     wm.valid_len = torch.tensor([3000, 2, 0, 1500], dtype=torch.int32, device="cuda")
-    check_multi(wm)
+    ref_m, _ = check_multi(wm)
+    out2, _ = ta.decode_two_pass(wm.q, wm.K, wm.V, wm.scale, wm.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert row_rel_l2(out2.cpu().numpy(), ref_m) <= TOL_BF16_F32OUT
     w = W.make_qkv(5, 71, 1, d, 5000, torch.bfloat16, seed=87, device="cuda")       # multi-query, 71 heads
     w.valid_len = torch.tensor([5000, 17, 0, 2500, 1], dtype=torch.int32, device="cuda")
     check(w)
