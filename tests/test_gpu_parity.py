@@ -27,10 +27,11 @@ import torch
 import oracle
 import paper_2408_04093_amd as ta
 import ta_workloads as W
+from bf16_rule import TOL_BF16, TOL_BF16_F32OUT, check_bf16_output
 
 pytestmark = pytest.mark.gpu
 
-TOL_BF16, TOL_BF16_F32OUT, TOL_F32, TOL_LSE = 2e-3, 5e-5, 1e-5, 1e-4
+TOL_F32, TOL_LSE = 1e-5, 1e-4
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -66,28 +67,6 @@ def gpu_decode(w, out_dtype=None):
     out, lse = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, out_dtype)
     torch.cuda.synchronize()
     return out.float().cpu().numpy(), lse.cpu().numpy()
-
-
-def bf16_ordinal(x):
-    """Map bf16 values (given as float arrays holding exact bf16) to integers monotone in value."""
-    bits = (np.asarray(x, np.float32).view(np.uint32) >> 16).astype(np.int64)
-    return np.where(bits & 0x8000, -(bits & 0x7fff), bits & 0x7fff)
-
-
-def check_bf16_output(out_b, out_f32, ref_out):
-    rne = torch.from_numpy(np.ascontiguousarray(out_f32)).to(torch.bfloat16).float().numpy()
-    np.testing.assert_array_equal(out_b, rne)
-    ref_b = torch.from_numpy(np.ascontiguousarray(ref_out)).to(torch.bfloat16).float().numpy()
-    ulp = np.abs(bf16_ordinal(out_b) - bf16_ordinal(ref_b))
-    # elements far below the row's scale carry the row's absolute fp32 error, which is many of THEIR ulps
-    rms = np.sqrt((ref_out ** 2).mean(axis=-1, keepdims=True))
-    small = np.abs(out_b - ref_b) <= 1e-4 * rms
-    assert ((ulp <= 1) | small).all()
-    # a different code is legitimate only where the exact value sits on a rounding boundary
-    boundary = 0.5 * (out_b.astype(np.float64) + ref_b)
-    assert ((ulp == 0) | small | (np.abs(ref_out - boundary) <= 4 * TOL_BF16_F32OUT * rms)).all()
-    if ref_out.size >= 2048:
-        assert np.linalg.norm(out_b - ref_out) / np.linalg.norm(ref_out) <= TOL_BF16
 
 
 def check(w, ref=None, f32_out_tol=None):
@@ -477,6 +456,23 @@ def test_config1_llama_128k_full():
     w = W.llama128k(device="cuda")
     assert w.shape == (1, 32, 8, 128, 131072)
     check(w)
+
+
+@pytest.mark.parametrize("seed_offset", [1, 2, 3])
+def test_config1_llama_128k_other_seeds(seed_offset):
+    """The headline shape on three more draws: the bf16-output rel-L2 of this 4096-element tensor sits
+    close to the 2e-3 bar by construction (it is the rounding to 8 bits itself), so the margin is
+    measured on several seeds, not one.  The figures are printed (-s) and recorded in the design doc."""
+    w = W.llama128k(device="cuda", seed_offset=seed_offset)
+    ref_out, ref_lse = oracle_of(w)
+    out, lse = check(w, ref=(ref_out, ref_lse))
+    out_b, _ = gpu_decode(w, ta.TA_BF16)
+    rel_b = float(np.linalg.norm(out_b - ref_out) / np.linalg.norm(ref_out))
+    rel_f = float(np.linalg.norm(out - ref_out) / np.linalg.norm(ref_out))
+    rne_ref = torch.from_numpy(ref_out).to(torch.bfloat16).float().numpy()
+    rel_rne = float(np.linalg.norm(rne_ref - ref_out) / np.linalg.norm(ref_out))
+    print(f"seed_offset {seed_offset}: rel-L2 bf16 out {rel_b:.6f}  RNE(oracle) alone {rel_rne:.6f}  fp32 out {rel_f:.2e}")
+    assert rel_b <= TOL_BF16
 
 
 def test_config2_ragged_batch_full():

@@ -49,5 +49,26 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert rec["config"]["workload"] == "llama128k" and rec["vs_baseline"] is None
     rf = rec["roofline"]
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    # HBM traffic is replayed from a committed profile: it must say so, or be null when the kernel changed since
+    assert rf["traffic"] is None or ("source" in rf["traffic"] and "kernel_source_sha16" in rf["traffic"])
+    st = rec["us_per_step_stats"]
+    assert st["min"] <= st["median"] <= st["p90"] <= st["max"] and st["min"] > 0
     assert rec["cpu_baseline"]["kind"] == "oracle" and rec["cpu_baseline"]["cores"] >= 1
-    assert rec["parity_vs_oracle"]["lse_abs"] <= 1e-4
+    assert rec["parity_vs_oracle"]["lse_abs"] <= 1e-4 and rec["parity_vs_oracle"]["rel_l2_bf16_out"] <= 2e-3
+
+
+@pytest.mark.gpu
+def test_bench_reports_the_matrix_core_roofline_where_it_binds_and_the_extra_workloads():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "llama128k_sq64", "--steps", "3",
+                        "--warmup", "1", "--no-extra", "--no-cpu-baseline"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    rec = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
+    rf = rec["roofline"]      # 256 rows per kv head: 384 flop/byte, beyond the 312 flop/byte ridge
+    assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0 and rf["flop_per_byte"] > 312
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "4", "--warmup", "2"],
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    rec = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
+    assert set(rec["also"]) == {"million", "ragged", "combine", "llama128k_sq16", "llama128k:energy"}
+    for k, v in rec["also"].items():
+        assert v["roofline"]["bound"] == "hbm" and v["value"] > 0 and v["config"]["workload"] in k
