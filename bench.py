@@ -45,6 +45,10 @@ def build_workload(name, device, copy):
     if name == "d64_256k":
         # head dimension 64 at the headline shape's byte count (the matrix-core kernel's 64-bit-load form)
         return W.llama128k(N=262144, d=64, device=device, seed_offset=7 + copy)
+    if name in ("f32_64k", "f32_d64_128k"):
+        # fp32 K/V (the vector-ALU kernel) at the headline shape's byte count
+        d = 128 if name == "f32_64k" else 64
+        return W.make_qkv(1, 32, 8, d, 65536 * (128 // d), torch.float32, W.BASE_SEED + 8 + 1000 * copy, device, name=name)
     if name == "million":
         return W.million(device=device)
     if name == "ragged":
@@ -350,7 +354,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "d64_256k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16", "llama128k_sq32", "llama128k_sq64"])
+    ap.add_argument("--workload", default="llama128k", choices=["llama128k", "million", "ragged", "combine", "shard80k", "shard40k", "d64_256k", "f32_64k", "f32_d64_128k", "llama128k_sq4", "llama128k_sq8", "llama128k_sq16", "llama128k_sq32", "llama128k_sq64"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--op", default="decode", choices=["decode", "energy", "two_pass"],
                     help="decode = ta_decode (the benchmarked path); energy = ta_energy (lse only, K only); "

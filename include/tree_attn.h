@@ -200,7 +200,6 @@ ta_status ta_decode_noalloc(const ta_problem *p, const void *q, const void *K, c
  * batches take the same equal-cost shares as in ta_decode.
  *   workspace   as for ta_decode (same size and alignment)
  *   lse         fp32 [B,Hq] ([B,Sq,Hq])
- * bf16 only (TA_ERR_UNSUPPORTED otherwise).
  */
 ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
                     void *workspace, size_t workspace_bytes, float *lse, void *stream);
@@ -213,7 +212,7 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
  * partials add up plainly.  K is streamed twice (1.5 x the bytes of ta_decode);
  * it exists as an on-GPU cross-check of Observation 1 and for callers that
  * already hold lse.  Arguments as for ta_decode.  A ragged batch takes the
- * equal-cost shares of ta_decode in both passes.  bf16 only.
+ * equal-cost shares of ta_decode in both passes.
  */
 ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, const void *V,
                              void *workspace, size_t workspace_bytes,

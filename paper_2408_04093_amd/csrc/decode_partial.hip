@@ -20,6 +20,10 @@
 //   * All GT query heads that share the KV head are scored against the same
 //     registers: every K/V byte is fetched once per group.
 //
+// Pass modes (the paper's Algorithm 3 against its Algorithms 1 and 2), as on the matrix-core kernel:
+//   kFull (m, l, o) per chunk; kEnergy (m, l) only, K is the only stream; kGradient
+//   o = sum_a exp(s_a - lse) v_a with the final lse given (no running max, no normaliser).
+//
 // Arithmetic
 //   q.k and the running max in fp64 (full rate on gfx950) so that large
 //   |score| does not cost precision; exponentials and sums in fp32.
@@ -58,6 +62,8 @@ __device__ __forceinline__ double lane_dot(const v4i &k, const double (&q)[4]) {
     return acc;
 }
 
+enum { kFull = 0, kEnergy = 1, kGradient = 2 };
+
 template <int U>
 struct Tile {
     v4i k[U];
@@ -76,7 +82,7 @@ __device__ __forceinline__ acc_t neg_inf() { return -__builtin_huge_val(); }
 // One pipeline step: U keys per row group, GT heads.
 //   row0: chunk-relative index of this lane's first key (u = 0); key u is
 //   row0 + u*RPW.  MASKED steps treat rows >= n as absent.
-template <int D, int GT, int U, bool MASKED>
+template <int D, int GT, int U, bool MASKED, int MODE>
 __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4], State<GT> &st, acc_t c, int row0,
                                      int n) {
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
@@ -94,17 +100,20 @@ __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4],
     }
 
     // Raise the running max only when some lane of the wave needs it; once the
-    // stream is warm this is rare and the rescale of o is skipped.
+    // stream is warm this is rare and the rescale of o is skipped.  (Gradient pass: the shift is the
+    // given logsumexp and never moves.)
     acc_t mt[GT];
     bool need = false;
+    if constexpr (MODE != kGradient) {
 #pragma unroll
-    for (int h = 0; h < GT; ++h) {
-        mt[h] = s2[0][h];
+        for (int h = 0; h < GT; ++h) {
+            mt[h] = s2[0][h];
 #pragma unroll
-        for (int u = 1; u < U; ++u) mt[h] = fmax(mt[h], s2[u][h]);
-        need |= mt[h] > st.m[h];
+            for (int u = 1; u < U; ++u) mt[h] = fmax(mt[h], s2[u][h]);
+            need |= mt[h] > st.m[h];
+        }
     }
-    if (__builtin_amdgcn_ballot_w64(need) != 0) {
+    if (MODE != kGradient && __builtin_amdgcn_ballot_w64(need) != 0) {
 #pragma unroll
         for (int h = 0; h < GT; ++h) {
             const bool up = mt[h] > st.m[h];
@@ -120,20 +129,22 @@ __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4],
     for (int u = 0; u < U; ++u) {
         float vf[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) vf[e] = __int_as_float(T.v[u][e]);
+        for (int e = 0; e < EPL; ++e) vf[e] = MODE != kEnergy ? __int_as_float(T.v[u][e]) : 0.f;
 #pragma unroll
         for (int h = 0; h < GT; ++h) {
             float p = exp2_hw((float)(s2[u][h] - st.m[h]));
             if constexpr (MASKED)
                 if (row0 + u * RPW >= n) p = 0.f;
             st.l[h] += p;
+            if constexpr (MODE != kEnergy) {
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) st.o[h][e] = fmaf(p, vf[e], st.o[h][e]);
+                for (int e = 0; e < EPL; ++e) st.o[h][e] = fmaf(p, vf[e], st.o[h][e]);
+            }
         }
     }
 }
 
-template <int D, int GT, int U>
+template <int D, int GT, int U, int MODE>
 __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
     constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
@@ -153,11 +164,15 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
     const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
     if (n <= 0) {   // empty chunk: the identity of the merge
-        for (int i = tid; i < GT * D; i += kThreads)
-            a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
-        if (tid < GT) {
-            a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
-            a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+        if constexpr (MODE != kEnergy) {
+            for (int i = tid; i < GT * D; i += kThreads)
+                a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
+        }
+        if constexpr (MODE != kGradient) {
+            if (tid < GT) {
+                a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
+                a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+            }
         }
         return;
     }
@@ -197,9 +212,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, kAux);
+            if constexpr (MODE != kEnergy) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, kAux);
+                for (int u = 0; u < U; ++u)
+                    T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, kAux);
+            }
         } else {
             // ragged last step: rows past the chunk are redirected to its last
             // row (always in range) and masked out of the arithmetic
@@ -212,9 +229,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, kAux);
+            if constexpr (MODE != kEnergy) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, kAux);
+                for (int u = 0; u < U; ++u)
+                    T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, kAux);
+            }
         }
     };
 
@@ -223,6 +242,12 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     for (int h = 0; h < GT; ++h) {
         st.m[h] = neg_inf();
         st.l[h] = 0.f;
+        if constexpr (MODE == kGradient) {
+            // the shift is the given total logsumexp (natural log -> log2 units); a row with no key at
+            // all (lse = -inf) gets +inf so that every exponential below is exactly 0
+            const float given = a.lse_in[(int64_t)b * a.Hq + hq0 + h];
+            st.m[h] = given == -__builtin_huge_valf() ? __builtin_huge_val() : (acc_t)given * (acc_t)kLog2e;
+        }
 #pragma unroll
         for (int e = 0; e < EPL; ++e) st.o[h][e] = 0.f;
     }
@@ -230,8 +255,8 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
     auto compute = [&](const Tile<U> &T, int it) {
         const int row0 = it * ROWS_ITER + row_lane;
-        if (it < n_full) step<D, GT, U, false>(T, q, st, c, row0, n);
-        else step<D, GT, U, true>(T, q, st, c, row0, n);
+        if (it < n_full) step<D, GT, U, false, MODE>(T, q, st, c, row0, n);
+        else step<D, GT, U, true, MODE>(T, q, st, c, row0, n);
     };
 
     // two register tiles, ping-pong: the loads of step it+1 are in flight
@@ -296,19 +321,27 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         const acc_t resid = fma(-(acc_t)m_nat, (acc_t)kLog2e, ms);
         const float fix = exp2_hw((float)resid);
         const int64_t pidx = pidx0 + (int64_t)h * a.P;
-        a.part_o[pidx * D + col] = ot * fix;
-        if (col == 0) {
-            a.part_m[pidx] = m_nat;
-            a.part_l[pidx] = lt * fix;
+        if constexpr (MODE == kGradient) {
+            a.part_o[pidx * D + col] = ot;   // weights were final all along: the shift is not stored
+        } else {
+            if constexpr (MODE == kFull) a.part_o[pidx * D + col] = ot * fix;
+            if (col == 0) {
+                a.part_m[pidx] = m_nat;
+                a.part_l[pidx] = lt * fix;
+            }
         }
     }
 }
 
 template <int D, int GT>
-hipError_t launch_one(const PartialArgs &a, hipStream_t s) {
+hipError_t launch_one(const PartialArgs &a, int mode, hipStream_t s) {
     constexpr int U = kKeysPerStep;
-    const int64_t blocks = launch_blocks(a);
-    return launch_kernel(decode_partial_kernel<D, GT, U>, dim3((uint32_t)blocks), dim3(kThreads), s, a);
+    const dim3 grid((uint32_t)launch_blocks(a));
+    switch (mode) {
+        case kEnergy: return launch_kernel(decode_partial_kernel<D, GT, U, kEnergy>, grid, dim3(kThreads), s, a);
+        case kGradient: return launch_kernel(decode_partial_kernel<D, GT, U, kGradient>, grid, dim3(kThreads), s, a);
+        default: return launch_kernel(decode_partial_kernel<D, GT, U, kFull>, grid, dim3(kThreads), s, a);
+    }
 }
 
 // resident workgroups per compute unit of one instantiation (register-bound)
@@ -316,7 +349,7 @@ template <int D, int GT>
 int occupancy_one() {
     static const int cached = [] {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kKeysPerStep>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kKeysPerStep, kFull>, kThreads, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
@@ -340,10 +373,10 @@ int occupancy_one() {
 
 }  // namespace
 
-hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s) {
+hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, int mode, hipStream_t s) {
     if (dtype != TA_F32) return hipErrorInvalidValue;   // bf16 belongs to the matrix-core kernel
     const int gt = a.g / a.slices;
-    TA_DISPATCH(launch_one, a, s);
+    TA_DISPATCH(launch_one, a, mode, s);
 }
 
 int decode_partial_occupancy(int dtype, int d, int gt) {

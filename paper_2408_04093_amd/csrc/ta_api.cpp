@@ -220,8 +220,7 @@ inline bool out_aligned(const void *out, int out_dtype) {
 }
 
 // Validate and launch one pass over the chunks.  mode: 0 = (m,l,o); 1 = energy pass (K only; V and
-// part_o unused); 2 = gradient pass given lse_in (part_m, part_l unused).  Modes 1 and 2 exist on
-// the matrix-core kernel only.
+// part_o unused); 2 = gradient pass given lse_in (part_m, part_l unused).
 ta_status run_partial(const ta_problem *p, const void *q, const void *K, const void *V, int32_t P,
                       const int64_t *chunk_bounds, float *part_m, float *part_l, float *part_o,
                       const float *lse_in, int mode, void *stream,
@@ -229,7 +228,6 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || (mode != 1 && !V)) return TA_ERR_NULL;
-    if (mode != 0 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if (P < 1 || P > (1 << 20)) return TA_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(K) || (V && !aligned16(V))) return TA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(part_m) | reinterpret_cast<uintptr_t>(part_l) |
@@ -246,7 +244,7 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     if (launch_blocks(a) >= ((int64_t)1 << 31)) return TA_ERR_SHAPE;
     const hipError_t e = use_mfma_path(p->qkv_dtype, p->d)
                              ? launch_decode_partial_mfma(a, p->d, mode, static_cast<hipStream_t>(stream))
-                             : launch_decode_partial(a, p->qkv_dtype, p->d, static_cast<hipStream_t>(stream));
+                             : launch_decode_partial(a, p->qkv_dtype, p->d, mode, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? TA_OK : TA_ERR_HIP;
 }
 
@@ -403,13 +401,12 @@ ta_status ta_energy(const ta_problem *p, const void *q, const void *K,
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || !workspace || !lse) return TA_ERR_NULL;
-    if (!use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return TA_ERR_ALIGN;
     if (!aligned16(q) || !aligned16(K)) return TA_ERR_ALIGN;
     const int32_t P = suggest_chunks(p, device_compute_units());
     if (workspace_bytes_given < workspace_bytes(p, P)) return TA_ERR_WORKSPACE;
     if (use_balanced(p)) return run_balanced(p, q, K, nullptr, workspace, 1, nullptr, lse, stream);
-    if (P == 1)
+    if (P == 1 && use_mfma_path(p->qkv_dtype, p->d))   // the matrix-core kernel finishes a single chunk itself
         return run_partial(p, q, K, nullptr, 1, nullptr, nullptr, nullptr, nullptr, nullptr, 1, stream, nullptr, lse);
     const size_t bhp = (size_t)p->B * tokens(p) * p->Hq * (size_t)P;
     float *part_m = static_cast<float *>(workspace) + bhp * p->d;      // same slots as in ta_decode
@@ -429,7 +426,6 @@ ta_status ta_decode_two_pass(const ta_problem *p, const void *q, const void *K, 
     const ta_status st = check_problem(p);
     if (st != TA_OK) return st;
     if (!q || !K || !V || !workspace || !out || !lse) return TA_ERR_NULL;
-    if (!use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !out_aligned(out, p->out_dtype)) return TA_ERR_ALIGN;
     const ta_status s1 = ta_energy(p, q, K, workspace, workspace_bytes_given, lse, stream);
     if (s1 != TA_OK) return s1;

@@ -79,7 +79,8 @@ inline int heads_per_workgroup(int dtype, int d, int g) {
 // workgroups of a chunked launch
 inline int64_t launch_blocks(const PartialArgs &a) { return (int64_t)a.bh_launch * a.slices * a.P; }
 
-hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, hipStream_t s);
+// fp32 K/V on the vector ALU; mode as below
+hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, int mode, hipStream_t s);
 // resident workgroups per compute unit of the decode_partial instantiation for (dtype, d, heads per workgroup)
 int decode_partial_occupancy(int dtype, int d, int gt);
 // bf16, d in {64, 128}.  mode: 0 = (m,l,o), 1 = energy pass (m,l; K only), 2 = gradient pass given lse (o only)

@@ -145,8 +145,7 @@ def test_energy_and_two_pass_argument_checks(lib):
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, None, FAKE, need, FAKE, FAKE, None) == 1
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4   # checked before any launch
     assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4
-    p.qkv_dtype = ta.TA_F32      # the energy / two-pass routes exist on the bf16 d=128 kernel only
-    p.k_stride_n = p.v_stride_n = 128
+    p.qkv_dtype, p.Sq = ta.TA_F32, 2      # fp32 K/V: one query token per sequence only
     assert ta.ta_energy(p, FAKE, FAKE, FAKE, 1 << 30, FAKE, None) == 6
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
 

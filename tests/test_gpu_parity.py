@@ -736,10 +736,28 @@ def test_energy_of_an_empty_sequence_and_unsupported_types():
     torch.cuda.synchronize()
     assert torch.isneginf(lse[0]).all() and torch.isfinite(lse[1]).all()
     assert not out[0].any().item() and torch.isfinite(out).all()
-    w32 = W.make_qkv(1, 2, 1, 64, 64, torch.float32, seed=2, device="cuda")
+    w32 = W.make_multi(1, 2, 2, 1, 64, 64, torch.float32, seed=2, device="cuda")   # several tokens need bf16
     with pytest.raises(ta.TAError) as e:
         ta.energy(w32.q, w32.K, w32.scale)
     assert e.value.code == 6
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,d,q_mult", [(1, 1, 1, 4096, 64, 1.0), (1, 1, 1, 4096, 64, 20.0), (2, 8, 2, 3001, 128, 1.0),
+                                                  (3, 16, 2, 700, 64, 1.0), (1, 6, 3, 5, 128, 1.0), (1, 32, 8, 20000, 128, 1.0)])
+def test_fp32_energy_and_two_pass_match_the_oracle(B, Hq, Hkv, N, d, q_mult):
+    """Algorithm 1 (lse alone, K only) and Algorithms 1 + 2 on fp32 K/V: the vector-ALU kernel's energy and
+    gradient modes, at the fp32 bar (1e-5 rel-L2, 1e-4 on lse), the overflow-stability config included."""
+    w = W.make_qkv(B, Hq, Hkv, d, N, torch.float32, seed=4100 + N, device="cuda", q_mult=q_mult)
+    if B > 1:
+        w.valid_len = torch.tensor([N, 0, N // 3][:B], dtype=torch.int32, device="cuda")
+    ref_out, ref_lse = oracle_of(w)
+    lse = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    out2, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    np.testing.assert_array_equal(lse2.cpu().numpy(), lse.cpu().numpy())
+    assert torch.isfinite(out2).all()
+    assert row_rel_l2(out2.cpu().numpy(), ref_out) <= TOL_F32
 
 
 def test_d64_heads_256k_full():
