@@ -56,19 +56,26 @@ constexpr int kMaxHeads = 16;
 // K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
 
 // Per-wave row statistics handed through LDS when the waves of a workgroup are merged.
+template <int NRB>
 struct WaveStats {
-    float m[kWaves][kMaxHeads];   // shift the wave's l and o are relative to (log2 units)
-    float t[kWaves][kMaxHeads];   // true row maximum seen by the wave
-    float l[kWaves][kMaxHeads];   // normaliser
-    float f[kWaves][kMaxHeads];   // weight of the wave's numerators in the merged row
-    float fin[kMaxHeads];         // the merged row's final factor (partial) or normaliser (direct result)
+    static constexpr int kRows = 16 * NRB;
+    float m[kWaves][kRows];   // shift the wave's l and o are relative to (log2 units)
+    float t[kWaves][kRows];   // true row maximum seen by the wave
+    float l[kWaves][kRows];   // normaliser
 };
+
+// LDS of a workgroup: the waves' K staging areas while the chunk is streamed; afterwards the same
+// memory carries the numerators that change owner in the merge (three quarters of them).
+template <int D, int NRB>
+constexpr int smem_bytes() {
+    return kWaves * Geo<D>::kStage > 3 * 16 * NRB * D * 4 ? kWaves * Geo<D>::kStage : 3 * 16 * NRB * D * 4;
+}
 
 // The whole streaming computation for one range: called once per workgroup by the chunked kernel
 // and once per piece by the balanced kernel.  smem / st are the workgroup's LDS areas.
 template <int D, int MODE, int NRB, bool BALANCED, int AUX = kAuxStream>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &rg, char *smem,
-                                              WaveStats &st) {
+                                              WaveStats<NRB> &st) {
     using G_ = Geo<D>;
     using row_t = typename G_::row_t;
     constexpr int kCols = G_::kCols, kSteps = G_::kSteps, kPitch = G_::kPitch, kStage = G_::kStage;
@@ -443,111 +450,183 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         back(std::true_type{}, vr, it);
     }
 
-    // ---- merge the waves through LDS, one row block at a time (the K staging area is free now).
-    // Three phases per block: (1) every wave stores its numerators (all 16 rows, 128-bit stores)
-    // and row statistics; (2) one thread per row merges the statistics, stores the row's scalars
-    // and leaves the waves' weights and the row's final factor in LDS; (3) all threads sum the
-    // numerators column by column, with every LDS read of the unrolled row loop in flight at once.
-    float *lds_o = reinterpret_cast<float *>(smem);   // [kWaves][16][D]
-    constexpr int kRowsPerPass = kThreads / D, kPasses = 16 / kRowsPerPass;
+    // ---- merge the four waves (each holds every row over its own keys) through LDS as a
+    // reduce-scatter.  The accumulators are cut into four units (row block rb, group ig of IW of the
+    // lane's four rows 4r + i), unit u owned by wave u.  (A) every wave publishes its row statistics;
+    // (B) every lane derives the weight of its wave in each of its rows (and the factor that moves
+    // the row to the stored maximum), scales its accumulators in registers and writes the three
+    // units it does not own to LDS as 128-bit lines; (C) the owner adds the three other waves'
+    // lines to its own registers and stores the result: whole rows, a lane's kCols adjacent columns
+    // at a time (16 lanes cover a row).  Two barriers, 3/4 of the numerators written and read once,
+    // all of it 128-bit wide.
+    constexpr int kRows = 16 * NRB;
+    constexpr int kUnitsPerBlock = kWaves / NRB;           // row groups per row block: 4, 2, 1
+    constexpr int IW = 4 / kUnitsPerBlock;                  // rows of a lane per unit: 1, 2, 4
+    constexpr int kVec = IW * kCols / 4;                    // IW rows x kCols columns = kVec 128-bit lines per lane and unit
+    f32x4 *lds_x = reinterpret_cast<f32x4 *>(smem);         // [owner][slot 0..2][kVec][lane]
+    const float ninf = -__builtin_huge_valf();
+    __syncthreads();                                        // every wave has left its K staging area
+    float lw[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        const int brows = nrows - 16 * rb < 16 ? nrows - 16 * rb : 16;   // rows of this block
-        if (brows <= 0) break;
-        // the row's normaliser is spread over the 4 row groups of the wave
-        float lw = l_run[rb];
-        lw = rows_sum(lw);
-        __syncthreads();
-        if constexpr (MODE != kEnergy) {
+        lw[rb] = rows_sum(l_run[rb]);                       // the normaliser is spread over the 4 row groups
+        if (r == 0) {
+            st.m[w][16 * rb + c] = m_run[rb];
+            st.t[w][16 * rb + c] = m_true[rb];
+            st.l[w][16 * rb + c] = lw[rb];
+        }
+    }
+    __syncthreads();
+
+    // (B) scalars of the rows, one thread per row; nothing below waits for them
+    if constexpr (MODE != kGradient) {
+        if (tid < nrows) {
+            const int h = tid;
+            float ms = st.m[0][h], mt = st.t[0][h];   // common shift of the merge, true maximum
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float *dst = lds_o + (w * 16 + 4 * r + i) * D + kCols * c;
+            for (int ww = 1; ww < kWaves; ++ww) {
+                ms = fmaxf(ms, st.m[ww][h]);
+                mt = fmaxf(mt, st.t[ww][h]);
+            }
+            const int64_t vrow = (int64_t)b * HqV + vhead(h);
+            const int64_t pidx = pindex(h);
+            if (ms == ninf) {   // this row saw no key of the chunk (causal limit)
+                if (direct) {
+                    a.lse_out[vrow] = ms;
+                } else {
+                    a.part_m[pidx] = ms;
+                    a.part_l[pidx] = 0.f;
+                }
+            } else {
+                float lt = 0.f;
 #pragma unroll
-                for (int j = 0; j < kCols; j += 4)
-                    *reinterpret_cast<f32x4 *>(dst + j) =
-                        f32x4{acc[rb][j][i], acc[rb][j + 1][i], acc[rb][j + 2][i], acc[rb][j + 3][i]};
+                for (int ww = 0; ww < kWaves; ++ww) {
+                    const float mw = st.m[ww][h];
+                    lt = fmaf((mw == ms) ? 1.0f : exp2_hw(mw - ms), st.l[ww][h], lt);
+                }
+                if (direct) {   // single chunk: Algorithm 3 step 6 right here
+                    a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
+                } else {
+                    // the stored m is the true maximum in natural-log units; l and o, so far relative
+                    // to the shift ms, are moved to the value actually stored (this also absorbs its
+                    // rounding)
+                    const float m_nat = mt * (float)kLn2;
+                    a.part_m[pidx] = m_nat;
+                    a.part_l[pidx] = lt * exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
+                }
             }
         }
-        if (r == 0) {
-            st.m[w][c] = m_run[rb];
-            st.t[w][c] = m_true[rb];
-            st.l[w][c] = lw;
-        }
-        __syncthreads();
+    }
 
-        if constexpr (MODE != kGradient) {
-            if (tid < brows) {   // one thread per row
-                const int h = tid;
-                float ms = st.m[0][h], mt = st.t[0][h];   // common shift of the merge, true maximum
+    if constexpr (MODE != kEnergy) {
+        // (B) weight of this wave in row 16 rb + c (the row this lane serves as row lane), handed to the
+        // lanes that hold the row's numerators (rows 4r + i of lane (r, .)) and applied in registers
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float scale = 1.0f;   // gradient pass: weights were final all along, the waves' numerators simply add
+            if constexpr (MODE != kGradient) {
+                const int h = 16 * rb + c;
+                float ms = st.m[0][h], mt = st.t[0][h], lt = 0.f;
 #pragma unroll
                 for (int ww = 1; ww < kWaves; ++ww) {
                     ms = fmaxf(ms, st.m[ww][h]);
                     mt = fmaxf(mt, st.t[ww][h]);
                 }
-                const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
-                const int64_t pidx = pindex(16 * rb + h);
-                float f[kWaves], lt = 0.f, fin;
-                if (ms == -__builtin_huge_valf()) {   // this row saw no key of the chunk (causal limit)
-#pragma unroll
-                    for (int ww = 0; ww < kWaves; ++ww) f[ww] = 0.f;
-                    fin = direct ? 1.0f : 0.f;        // numerators are all 0: out = 0 / 1, o = 0 * 0
-                    if (direct) {
-                        a.lse_out[vrow] = ms;
-                    } else {
-                        a.part_m[pidx] = ms;
-                        a.part_l[pidx] = 0.f;
-                    }
-                } else {
+                const float mine = m_run[rb];
+                if (ms == ninf) {
+                    scale = 0.f;             // the numerators are all 0 (and stay 0)
+                } else if (direct) {
 #pragma unroll
                     for (int ww = 0; ww < kWaves; ++ww) {
                         const float mw = st.m[ww][h];
-                        f[ww] = (mw == ms) ? 1.0f : exp2_hw(mw - ms);
-                        lt = fmaf(f[ww], st.l[ww][h], lt);
+                        lt = fmaf((mw == ms) ? 1.0f : exp2_hw(mw - ms), st.l[ww][h], lt);
                     }
-                    if (direct) {   // single chunk: Algorithm 3 step 6 right here
-                        fin = lt;
-                        a.lse_out[vrow] = fmaf(ms, (float)kLn2, logf(lt));
-                    } else {
-                        // the stored m is the true maximum in natural-log units; l and o, so far relative
-                        // to the shift ms, are moved to the value actually stored (this also absorbs its
-                        // rounding)
-                        const float m_nat = mt * (float)kLn2;
-                        fin = exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
-                        a.part_m[pidx] = m_nat;
-                        a.part_l[pidx] = lt * fin;
-                    }
+                    scale = ((mine == ms) ? 1.0f : exp2_hw(mine - ms)) / lt;   // out = o / l
+                } else {
+                    const float m_nat = mt * (float)kLn2;
+                    scale = ((mine == ms) ? 1.0f : exp2_hw(mine - ms)) * exp2_hw(fmaf(-m_nat, (float)kLog2e, ms));
                 }
-#pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) st.f[ww][h] = f[ww];
-                st.fin[h] = fin;
             }
-            if constexpr (MODE == kFull) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float si = MODE == kGradient ? 1.0f : __shfl(scale, (lane & 48) | (4 * r + i));
+#pragma unroll
+                for (int j = 0; j < kCols; ++j) acc[rb][j][i] *= si;
+            }
         }
-
-        if constexpr (MODE != kEnergy) {
-            const int col = tid % D;
+        // (B) the three units this wave does not own go to their owners
 #pragma unroll
-            for (int ps = 0; ps < kPasses; ++ps) {
-                const int h = tid / D + ps * kRowsPerPass;
-                const int hc = h < brows ? h : brows - 1;   // rows beyond the block repeat its last row, unstored
-                float ot = 0.f;
+        for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll
-                for (int ww = 0; ww < kWaves; ++ww) {
-                    const float x = lds_o[(ww * 16 + hc) * D + col];
-                    // gradient pass: weights were final all along, the waves' numerators simply add
-                    if constexpr (MODE == kGradient) ot += x;
-                    else ot = fmaf(st.f[ww][hc], x, ot);
+            for (int ig = 0; ig < kUnitsPerBlock; ++ig) {
+                const int owner = rb * kUnitsPerBlock + ig;
+                if (owner != w) {
+                    const int slot = (w - owner - 1) & 3;   // 0..2
+                    f32x4 *dst = lds_x + ((owner * 3 + slot) * kVec) * kWave + lane;
+                    // IW rows x kCols columns of the lane, flattened (ii, j) -> lines of four floats
+#pragma unroll
+                    for (int v = 0; v < kVec; ++v) {
+                        f32x4 x;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int flat = 4 * v + e, ii = flat / kCols, j = flat % kCols;
+                            x[e] = acc[rb][j][ig * IW + ii];
+                        }
+                        dst[v * kWave] = x;
+                    }
                 }
-                if (h < brows) {
-                    if constexpr (MODE == kGradient) {
-                        a.part_o[pindex(16 * rb + h) * D + col] = ot;
-                    } else if (direct) {
-                        const int64_t vrow = (int64_t)b * HqV + vhead(16 * rb + h);
-                        const float z = ot / st.fin[hc];
-                        if (a.out_dtype == TA_BF16) reinterpret_cast<unsigned short *>(a.out)[vrow * D + col] = f32_to_bf16_rne(z);
-                        else reinterpret_cast<float *>(a.out)[vrow * D + col] = z;
-                    } else {
-                        a.part_o[pindex(16 * rb + h) * D + col] = ot * st.fin[hc];
+            }
+        }
+    }
+    if constexpr (MODE != kEnergy) {
+        __syncthreads();
+        // (C) the owner sums and stores
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+            for (int ig = 0; ig < kUnitsPerBlock; ++ig) {
+                const int owner = rb * kUnitsPerBlock + ig;
+                if (owner == w) {
+                    float o[IW][kCols];
+#pragma unroll
+                    for (int ii = 0; ii < IW; ++ii)
+#pragma unroll
+                        for (int j = 0; j < kCols; ++j) o[ii][j] = acc[rb][j][ig * IW + ii];
+                    f32x4 x[3][kVec];
+#pragma unroll
+                    for (int slot = 0; slot < 3; ++slot)
+#pragma unroll
+                        for (int v = 0; v < kVec; ++v) x[slot][v] = lds_x[((owner * 3 + slot) * kVec + v) * kWave + lane];
+#pragma unroll
+                    for (int slot = 0; slot < 3; ++slot)
+#pragma unroll
+                        for (int v = 0; v < kVec; ++v)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int flat = 4 * v + e;
+                                o[flat / kCols][flat % kCols] += x[slot][v][e];
+                            }
+#pragma unroll
+                    for (int ii = 0; ii < IW; ++ii) {
+                        const int h = 16 * rb + 4 * r + ig * IW + ii;
+                        if (h < nrows) {
+                            if (direct && MODE == kFull) {
+                                const int64_t vrow = (int64_t)b * HqV + vhead(h);
+                                if (a.out_dtype == TA_BF16) {
+                                    unsigned short *dst = reinterpret_cast<unsigned short *>(a.out) + vrow * D + kCols * c;
+#pragma unroll
+                                    for (int j = 0; j < kCols; ++j) dst[j] = f32_to_bf16_rne(o[ii][j]);
+                                } else {
+                                    float *dst = reinterpret_cast<float *>(a.out) + vrow * D + kCols * c;
+#pragma unroll
+                                    for (int j = 0; j < kCols; ++j) dst[j] = o[ii][j];
+                                }
+                            } else {
+                                float *dst = a.part_o + pindex(h) * D + kCols * c;
+#pragma unroll
+                                for (int j = 0; j < kCols; ++j) dst[j] = o[ii][j];
+                            }
+                        }
                     }
                 }
             }
@@ -562,8 +641,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 // others (64 query tokens at the llama shape: 256 us against 273 us per launch).
 template <int D, int MODE, int NRB, bool SHARED = false>
 __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, false)) decode_partial_mfma_kernel(const PartialArgs a) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
-    __shared__ WaveStats st;
+    __shared__ __attribute__((aligned(16))) char smem[smem_bytes<D, NRB>()];
+    __shared__ WaveStats<NRB> st;
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     if (cr.surplus) return;
@@ -588,8 +667,8 @@ constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty
 
 template <int D, int MODE, int NRB>
 __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, true)) decode_balanced_mfma_kernel(const PartialArgs a) {
-    __shared__ __attribute__((aligned(16))) char smem[kWaves * Geo<D>::kStage];
-    __shared__ WaveStats st;
+    __shared__ __attribute__((aligned(16))) char smem[smem_bytes<D, NRB>()];
+    __shared__ WaveStats<NRB> st;
     __shared__ int64_t sh_cum[kMaxBalancedB + 1];
     __shared__ int64_t sh_scan[kWaves];
     constexpr int kMinShare = kMinShareBytes / (2 * D), kPieceCost = kPieceCostBytes / (2 * D);   // in keys
