@@ -78,8 +78,12 @@ typedef enum { TA_BF16 = 0, TA_F32 = 1 } ta_dtype;
  *   q   [B,Hq,d]       contiguous  ([B,Sq,Hq,d] when Sq > 1)
  *   K,V [B,Hkv,N,d]    innermost stride 1; the other strides are given in
  *                      ELEMENTS and must keep every row 16-byte aligned
- *                      (stride_n >= d).  A whole [N,d] head slice must span
- *                      less than 4 GiB.
+ *                      (stride_n >= d).  A head slice may exceed 4 GiB; what must
+ *                      span less than 4 GiB is one CHUNK (row offsets inside a
+ *                      chunk are 32-bit): ta_suggest_chunks takes care of it,
+ *                      ta_decode_partial refuses a P that is too small, and with
+ *                      an explicit chunk table the whole slice must stay below
+ *                      4 GiB (TA_ERR_UNSUPPORTED otherwise).
  *   d in {64, 128};  Hq % Hkv == 0 (any group size Hq / Hkv, multi-query included).
  * bf16 inputs: scores and all sums are accumulated in fp32.
  * fp32 inputs: scores and the running max are accumulated in fp64, the

@@ -47,15 +47,22 @@ ta_status check_problem(const ta_problem *p) {
         if ((s * eb) % 16 != 0) return TA_ERR_ALIGN;
     }
     if (p->k_stride_n < p->d || p->v_stride_n < p->d) return TA_ERR_SHAPE;
-    // 32-bit byte offsets inside one [N, d] head slice
-    // (divisions, so that absurd N or strides cannot overflow the product)
-    const int64_t lim = (int64_t)1 << 32;
-    if (p->N >= lim / (p->k_stride_n * eb) + 1 || p->N >= lim / (p->v_stride_n * eb) + 1) return TA_ERR_UNSUPPORTED;
-    if (p->N * p->k_stride_n * eb >= lim || p->N * p->v_stride_n * eb >= lim) return TA_ERR_UNSUPPORTED;
+    // Row offsets inside ONE CHUNK are 32-bit (a chunk's base address is 64-bit), so a row must be
+    // shorter than 4 GiB here; that the chunks themselves span less is checked where they are chosen.
+    if (p->k_stride_n * eb >= ((int64_t)1 << 31) || p->v_stride_n * eb >= ((int64_t)1 << 31)) return TA_ERR_UNSUPPORTED;
+    if (p->N >= ((int64_t)1 << 40)) return TA_ERR_UNSUPPORTED;
     if (p->Sq < 0 || p->Sq > 4096) return TA_ERR_SHAPE;
     if (p->Sq > 1 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if ((int64_t)p->B * p->Hq * tokens(p) >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
     return TA_OK;
+}
+
+// Most keys a chunk (or a piece of the balanced launch) may hold: its rows must lie within 4 GiB
+// of its first row, whatever the row stride.
+inline int64_t max_chunk_keys(const ta_problem *p) {
+    const int64_t eb = elem_bytes(p->qkv_dtype);
+    const int64_t row = (p->k_stride_n > p->v_stride_n ? p->k_stride_n : p->v_stride_n) * eb;
+    return (((int64_t)1 << 32) - 1 - (int64_t)p->d * eb) / row;
 }
 
 int device_compute_units() {
@@ -142,6 +149,9 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
     const int64_t p_hi = (p->N + kMinChunk - 1) / kMinChunk;
     if (P > p_hi) P = p_hi;
     if (P < 1) P = 1;
+    // a head slice beyond 4 GiB: enough chunks that each stays within the reach of 32-bit row offsets
+    const int64_t cap = max_chunk_keys(p);
+    while ((p->N + P - 1) / P > cap) ++P;
     if (P > 65536) P = 65536;
     return (int32_t)P;
 }
@@ -156,6 +166,7 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
 // more groups than CUs when a sequence cannot exceed 4096 keys (at d = 128).
 inline bool use_balanced(const ta_problem *p) {
     if (p->valid_len == nullptr || !use_mfma_path(p->qkv_dtype, p->d) || p->B > balanced_max_batch()) return false;
+    if (p->N > max_chunk_keys(p)) return false;   // a piece may be a whole sequence
     const int64_t groups = launch_groups(p), cus = device_compute_units();
     if (groups <= cus) return true;
     return groups <= 4 * cus && p->N * p->d >= (int64_t)4096 * 128;
@@ -229,6 +240,8 @@ ta_status run_partial(const ta_problem *p, const void *q, const void *K, const v
     if (st != TA_OK) return st;
     if (!q || !K || (mode != 1 && !V)) return TA_ERR_NULL;
     if (P < 1 || P > (1 << 20)) return TA_ERR_SHAPE;
+    // every chunk within 4 GiB of its first row: equal chunks hold ceil(N / P) keys, a table may hold any
+    if ((chunk_bounds ? p->N : (p->N + P - 1) / P) > max_chunk_keys(p)) return TA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(K) || (V && !aligned16(V))) return TA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(part_m) | reinterpret_cast<uintptr_t>(part_l) |
          reinterpret_cast<uintptr_t>(part_o) | reinterpret_cast<uintptr_t>(lse_in)) & 3u)

@@ -98,7 +98,8 @@ def test_workspace_and_chunk_heuristic(lib):
     (lambda p: setattr(p, "k_stride_n", 132), 4),    # rows no longer 16-byte aligned
     (lambda p: setattr(p, "v_stride_n", 64), 2),     # rows overlap
     (lambda p: setattr(p, "scale", float("nan")), 2),
-    (lambda p: setattr(p, "N", 1 << 25), 6),         # head slice >= 4 GiB
+    (lambda p: setattr(p, "N", 1 << 41), 6),
+    (lambda p: setattr(p, "k_stride_n", 1 << 31), 6),   # a row of 4 GiB
     (lambda p: setattr(p, "Sq", -1), 2),
     (lambda p: (setattr(p, "Sq", 4), setattr(p, "qkv_dtype", 1)), 6),   # several tokens need bf16
 ])
@@ -226,6 +227,26 @@ def test_size_check_does_not_overflow(lib):
     assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
     p.N, p.k_stride_n = 1 << 20, 1 << 45
     assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
+
+
+def test_head_slices_beyond_4_gib_get_enough_chunks(lib):
+    # row offsets inside a chunk are 32-bit: a head slice of 8 GiB (2^25 keys of 256 bytes) needs >= 3 chunks
+    p = llama_problem()
+    p.B, p.Hq, p.Hkv, p.N = 1, 4, 1, 1 << 25
+    p.k_stride_h = p.v_stride_h = p.k_stride_b = p.v_stride_b = p.N * 128
+    P = ta.ta_suggest_chunks(p)
+    assert P >= 3 and -(-p.N // P) * 256 < 1 << 32
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 1, None, FAKE, FAKE, FAKE, None) == 6    # one chunk of 8 GiB
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 2, None, FAKE, FAKE, FAKE, None) == 6    # two of 4 GiB
+    assert ta.ta_decode_partial(p, FAKE, FAKE, FAKE, 64, FAKE, FAKE, FAKE, FAKE, None) == 6   # a table may hold any chunk
+    # many sequences, more groups than compute units: still never one chunk per sequence
+    p.B = 1024
+    p.k_stride_b = p.v_stride_b = p.N * 128
+    assert ta.ta_suggest_chunks(p) >= 3
+    # ragged: the balanced launch (a piece may be a whole sequence) is not taken
+    p.B, p.valid_len = 2, FAKE
+    P = ta.ta_suggest_chunks(p)
+    assert ta.ta_workspace_bytes(p, P) == -(-(2 * 4 * P * 130 * 4) // 256) * 256
 
 
 def test_missing_library_fails_loudly(monkeypatch):

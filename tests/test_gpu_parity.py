@@ -800,24 +800,61 @@ def test_batched_short_contexts_take_the_single_chunk_path(d):
     check_multi(wm)
 
 
-def test_largest_supported_head_slice():
-    """One [N, d] head slice just under the 4 GiB limit of the 32-bit row offsets (N = 2^24 - 8 keys)."""
+def test_largest_single_chunk():
+    """One chunk just under the 4 GiB reach of the 32-bit row offsets (N = 2^24 - 8 keys of 256 bytes)."""
     N = (1 << 24) - 8
     w = W.make_qkv(1, 2, 1, 128, N, torch.bfloat16, seed=91, device="cuda")
     p = ta.make_problem(w.q, w.K, w.V, w.scale)
-    assert ta.ta_suggest_chunks(p) > 0
-    p.N = 1 << 24                                  # one row more would need a 33-bit offset: refused on the host
-    assert ta.ta_suggest_chunks(p) == 0
-    out, lse = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, 1)           # the whole slice as ONE chunk
+    out, lse = ta.tree_combine(pm, pl, po)
     torch.cuda.synchronize()
     ref_out, ref_lse = oracle_of(w)
+    # 4 M keys per wavefront in one fp32 running sum, and outputs of size 1 / sqrt(N): the rounding of the
+    # sums (not of the addressing) shows at 1e-4 here; the library's own chunking is held to the usual bar
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= 5e-4
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    torch.cuda.synchronize()
     assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
     assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+    p.N = 1 << 24                                  # one row more would need a 33-bit offset: refused on the host
+    assert ta.ta_decode_partial(p, w.q.data_ptr(), w.K.data_ptr(), w.V.data_ptr(), 1, None, pm.data_ptr(), pl.data_ptr(),
+                                po.data_ptr(), None) == 6
     # the last rows really are read: poison the final key and the result must change
     w.K[0, 0, N - 1] = 40.0
     out2, lse2 = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
     torch.cuda.synchronize()
     assert not torch.equal(lse, lse2)
+
+
+def test_head_slice_beyond_4_gib():
+    """A head slice of 5.4 GB (21 M keys of 256 bytes): chunk bases are 64-bit, only offsets inside a chunk
+    are 32-bit, and the chunk heuristic never hands out a chunk of 4 GiB."""
+    N = (1 << 24) + (1 << 22) + 5
+    w = W.make_qkv(1, 2, 1, 128, N, torch.bfloat16, seed=92, device="cuda")
+    p = ta.make_problem(w.q, w.K, w.V, w.scale)
+    P = ta.ta_suggest_chunks(p)
+    assert P >= 2 and -(-N // P) * 256 < 1 << 32
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+    lse_e = ta.energy(w.q, w.K, w.scale)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle_of(w)
+    assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+    assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE and lse_err(lse_e.cpu().numpy(), ref_lse) <= TOL_LSE
+    # keys on both sides of the 4 GiB line are read: a spike just beyond it, and the very last key
+    for idx in ((1 << 24) + 100, N - 1):
+        w.K[0, 0, idx] = 40.0
+        _, lse2 = ta.decode(w.q, w.K, w.V, w.scale, out_dtype=ta.TA_F32)
+        torch.cuda.synchronize()
+        assert not torch.equal(lse, lse2)
+        lse = lse2
+    # two huge chunks (2.7 GB each) with a ragged length: the valid keys end inside the first
+    w.valid_len = torch.tensor([(1 << 23) + 12345], dtype=torch.int32, device="cuda")
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, 2, w.valid_len)
+    out3, lse3 = ta.tree_combine(pm, pl, po)
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle_of(w)
+    assert row_rel_l2(out3.cpu().numpy(), ref_out) <= 5e-4 and lse_err(lse3.cpu().numpy(), ref_lse) <= TOL_LSE
 
 
 @pytest.mark.parametrize("d", [128, 64])
