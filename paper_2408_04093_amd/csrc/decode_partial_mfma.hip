@@ -18,7 +18,9 @@
 //   K   global --(8 coalesced 128-bit nt loads: 16 lanes x 16 B = one row)-->
 //       VGPR --> LDS, row pitch 272 B --> VGPR in MFMA A layout
 //       (lane (kb = l/16, m = l%16) reads key m, bytes 16*(4t+kb) of step t;
-//       the 16-byte pad makes these reads bank-conflict-free).
+//       the 16-byte pad makes these reads bank-conflict-free).  With four row
+//       blocks the lanes load exactly those 16 bytes from global memory
+//       instead and LDS stays out of the loop (see kDirectK).
 //       S[key][head] = sum_t A_t(K) x B_t(Q^T): 2 key groups x 4 k-steps.
 //   D layout of S: lane (r = l/16, h = l%16) holds keys 16G + 4r + i of head h,
 //       i.e. each lane owns 8 keys of ONE head: exactly the A layout needed
@@ -80,6 +82,13 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     using row_t = typename G_::row_t;
     constexpr int kCols = G_::kCols, kSteps = G_::kSteps, kPitch = G_::kPitch, kStage = G_::kStage;
     constexpr int kLaneBytes = G_::kLaneBytes;
+    // How the K tile reaches MFMA A layout.  Staged (one to two row blocks): coalesced row loads,
+    // then through the wave's LDS area.  Direct (four row blocks): every lane loads its A operand's
+    // 16 bytes itself, 16 rows x 64 bytes per instruction.  The direct form keeps LDS out of the
+    // loop (8 writes, 8 reads and their waits per step: 220 against 236 us per launch at 256 rows, 87
+    // against 89-91 us at 64), but each cache line is requested twice; with one row block, where HBM
+    // is the bound, it measured 0.6 us slower at 128k keys, so the staged form stays there.
+    constexpr bool kDirectK = NRB == 4;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -226,15 +235,42 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
     };
 
+    // K straight into MFMA A layout: lane (kb = r, key m = c) of key group G and k-step t holds bytes
+    // 16 (4t + r) .. + 16 of key 16 G + c: 16-byte loads, 16 rows x 64 bytes per instruction
+    const uint32_t kdlane = (uint32_t)(w * kTile + c) * a.k_row_bytes + r * 16;
+    auto issue_kd_full = [&](v4i (&ka)[2][kSteps], int it) {
+#pragma unroll
+        for (int G = 0; G < 2; ++G)
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t)
+                ka[G][t] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)kdlane, (int)((uint32_t)(it * ROWS_ITER + 16 * G) * a.k_row_bytes + 64 * t), AUX);
+    };
+    auto issue_kd = [&](v4i (&ka)[2][kSteps], int it) {
+        if (it < n_full) {
+            issue_kd_full(ka, it);
+        } else {
+#pragma unroll
+            for (int G = 0; G < 2; ++G) {
+                int row = it * ROWS_ITER + w * kTile + 16 * G + c;
+                row = row < n ? row : n - 1;
+#pragma unroll
+                for (int t = 0; t < kSteps; ++t)
+                    ka[G][t] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)((uint32_t)row * a.k_row_bytes + (4 * t + r) * 16), 0, AUX);
+            }
+        }
+    };
+
     const float cs = fabsf((float)a.c);   // |scale| * log2(e); the sign sits in q
     float m_run[NRB];              // shift of this lane's row (log2 units): a past row maximum, at most kLazy
                                    // below the current one; same in all 4 row groups
-    float m_true[NRB];             // true running maximum of the row
+    float m_top[NRB];              // largest unscaled score this LANE has seen in its row (the row's true
+                                   // maximum is the maximum over its 4 lanes, taken once at the end)
+    float thr[NRB];                // (m_run + kLazy) / |c|: the unscaled score beyond which the shift must move
     float l_run[NRB];              // this lane's share of the row's normaliser
     f32x4 acc[NRB][kCols];         // acc[rb][j][i] = O[row 16rb + 4r + i][col kCols c + j]
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        m_run[rb] = m_true[rb] = -__builtin_huge_valf();
+        m_run[rb] = m_top[rb] = thr[rb] = -__builtin_huge_valf();
         l_run[rb] = 0.f;
         if constexpr (MODE == kGradient) {
             // the shift is the given total logsumexp (natural log -> log2 units); a row with no key
@@ -248,24 +284,25 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 
     // One pipeline step on the register tiles (kr, vr) holding step `it`, in two halves around the
     // only data-dependent decision, whether a running max must be raised:
-    //   front: K tile to LDS, next K tile in flight, S = K Q^T, scaled (and masked) scores, row maxima
+    //   front: K tile into A layout, next K tile in flight, S = K Q^T, (masked) scores, lane maxima
     //   back:  exponentials, P, O += P V, next V tile in flight
     // TAIL is a compile-time flag (std::true_type / std::false_type).  Steady steps (TAIL false) are
     // full tiles followed by another full tile: no masking arithmetic, and the next tile's loads are
     // issued unconditionally.  Tail steps mask rows beyond each row's limit and issue the next tile
     // only if there is one.
     float sv[NRB][8];   // unscaled scores q.k of the current step, slot e = 4G + i (-inf where masked)
-    float mx[NRB];      // row maxima of the current step, scaled (log2 units)
-    bool up[NRB];
+    float m8[NRB];      // largest of this lane's 8 unscaled scores of the current step
 
-    auto front = [&](auto tail_c, row_t (&kr)[8], int it) -> bool {
+    auto front = [&](auto tail_c, row_t (&kr)[8], v4i (&ka)[2][kSteps], int it) -> bool {
         constexpr bool masked = decltype(tail_c)::value;
-        // ---- K tile: registers -> LDS (row-major, padded) -> A layout
+        if constexpr (!kDirectK) {
+            // ---- K tile: registers -> LDS (row-major, padded), next tile requested
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            *reinterpret_cast<row_t *>(stage + trow[e] * kPitch + c * kLaneBytes) = kr[e];
-        if constexpr (!masked) issue_k_full(kr, it + 1);
-        else if (it + 1 < n_iters) issue_k(kr, it + 1);
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<row_t *>(stage + trow[e] * kPitch + c * kLaneBytes) = kr[e];
+            if constexpr (!masked) issue_k_full(kr, it + 1);
+            else if (it + 1 < n_iters) issue_k(kr, it + 1);
+        }
 
         // S = K Q^T.  The 2 key groups x NRB row blocks are independent accumulation chains; the
         // k-step loop is outermost so that consecutive MFMAs never depend on each other.
@@ -273,8 +310,10 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
         for (int G = 0; G < 2; ++G)
 #pragma unroll
-            for (int t = 0; t < kSteps; ++t)
-                af[G][t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
+            for (int t = 0; t < kSteps; ++t) {
+                if constexpr (kDirectK) af[G][t] = ka[G][t];
+                else af[G][t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
+            }
         f32x4 s[NRB][2];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) s[rb][0] = s[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -286,10 +325,15 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 for (int rb = 0; rb < NRB; ++rb)
                     s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[G][t]), qb[rb][t],
                                                                         s[rb][G], 0, 0, 0);
+        if constexpr (kDirectK) {   // the MFMAs above have read the tile: request the next one
+            if constexpr (!masked) issue_kd_full(ka, it + 1);
+            else if (it + 1 < n_iters) issue_kd(ka, it + 1);
+        }
 
-        // per row block this lane owns 8 keys of one row.  Done in phases over all row blocks
-        // (scores and lane max; the two cross-lane steps of the row max) so that the blocks'
-        // dependency chains interleave.
+        // per row block this lane owns 8 keys of one row.  The steady state needs no row maximum,
+        // only the knowledge that no score exceeds the shift by more than kLazy: a per-lane
+        // comparison against the row's threshold, and no cross-lane work at all (raise() does that
+        // on the rare step where some lane says yes).
         bool any_up = false;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -300,24 +344,15 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                     if (it * ROWS_ITER + w * kTile + trow[e] >= nlim[rb]) sv[rb][e] = -__builtin_huge_valf();
             }
             if constexpr (MODE != kGradient) {
-                float m8 = sv[rb][0];
+                float top = sv[rb][0];
 #pragma unroll
-                for (int e = 1; e < 8; ++e) m8 = fmaxf(m8, sv[rb][e]);
-                mx[rb] = m8 * cs;
-                if constexpr (masked)
-                    if (m8 == -__builtin_huge_valf()) mx[rb] = m8;   // keeps -inf * 0 out when scale is 0
+                for (int e = 1; e < 8; ++e) top = fmaxf(top, sv[rb][e]);
+                m8[rb] = top;
+                m_top[rb] = fmaxf(m_top[rb], top);
+                any_up |= top > thr[rb];   // also true on a row's first visible keys (thr = -inf)
             }
         }
-        if constexpr (MODE != kGradient) {
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) {
-                mx[rb] = rows_max(mx[rb]);
-                m_true[rb] = fmaxf(m_true[rb], mx[rb]);
-                up[rb] = mx[rb] > m_run[rb] + kLazy;   // also true on a row's first keys (-inf + kLazy = -inf)
-                any_up |= up[rb];
-            }
-            return __builtin_amdgcn_ballot_w64(any_up) != 0;
-        }
+        if constexpr (MODE != kGradient) return __builtin_amdgcn_ballot_w64(any_up) != 0;
         return false;
     };
 
@@ -326,8 +361,12 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     auto raise = [&]() {
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
-            const float alpha = up[rb] ? exp2_hw(m_run[rb] - mx[rb]) : 1.0f;
-            m_run[rb] = up[rb] ? mx[rb] : m_run[rb];
+            // row maximum of the step in log2 units (-inf stays -inf also when the scale is 0)
+            const float mx = rows_max(m8[rb] == -__builtin_huge_valf() ? m8[rb] : m8[rb] * cs);
+            const bool up = mx > m_run[rb] + kLazy;
+            const float alpha = up ? exp2_hw(m_run[rb] - mx) : 1.0f;
+            m_run[rb] = up ? mx : m_run[rb];
+            thr[rb] = (m_run[rb] + kLazy) / cs;   // +inf when the scale is 0: the shift never moves again
             l_run[rb] *= alpha;
             if constexpr (MODE == kFull) {
                 // acc[rb][.][i] belongs to row 4r+i of the block, whose alpha sits in lane (r, 4r+i)
@@ -368,46 +407,53 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
     };
 
+    // Probabilities of one row block from its scores: p = 2^(s c - shift), the lane's share of the
+    // normaliser, and (unless only the energy is wanted) P = hi + lo as MFMA A operand: lane
+    // (r, row c), k = 8r + e.
+    auto make_p = [&](auto tail_c, int rb, bf16x8 &hi, bf16x8 &lo) {
+        constexpr bool masked = decltype(tail_c)::value;
+        float p[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = exp2_hw(fmaf(sv[rb][e], cs, -m_run[rb]));
+            if constexpr (masked)
+                if (sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;   // also when m_run is still -inf
+            l_run[rb] += p[e];
+        }
+        if constexpr (MODE != kEnergy) {
+            uint32_t ph[4], pl[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
+                const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
+                pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
+            }
+            hi = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
+            lo = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
+        }
+    };
+    // column j of the V tile in MFMA B layout: key pairs interleaved by one byte permute per
+    // register, the low (j even) or high (j odd) halves of the two keys' registers
+    auto v_operand = [&](row_t (&vr)[8], int j) {
+        uint32_t bj[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
+            bj[x] = __builtin_amdgcn_perm(v1, v0, (j & 1) ? 0x07060302u : 0x05040100u);
+        }
+        return __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
+    };
+
     auto back = [&](auto tail_c, row_t (&vr)[8], int it) {
         constexpr bool masked = decltype(tail_c)::value;
         bf16x8 pa_hi[NRB], pa_lo[NRB];
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            float p[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = exp2_hw(fmaf(sv[rb][e], cs, -m_run[rb]));
-                if constexpr (masked)
-                    if (sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;   // also when m_run is still -inf
-                l_run[rb] += p[e];
-            }
-            if constexpr (MODE != kEnergy) {
-                // P = hi + lo, both bf16, as MFMA A operand: lane (r, row c), k = 8r + e
-                uint32_t ph[4], pl[4];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
-                    const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
-                    pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
-                }
-                pa_hi[rb] = __builtin_bit_cast(bf16x8, v4i{(int)ph[0], (int)ph[1], (int)ph[2], (int)ph[3]});
-                pa_lo[rb] = __builtin_bit_cast(bf16x8, v4i{(int)pl[0], (int)pl[1], (int)pl[2], (int)pl[3]});
-            }
-        }
-
+        for (int rb = 0; rb < NRB; ++rb) make_p(tail_c, rb, pa_hi[rb], pa_lo[rb]);
         if constexpr (MODE != kEnergy) {
-            // ---- PV: for each of this lane's columns, interleave key pairs into B layout (once
-            // for all row blocks)
+            // ---- PV: each of this lane's columns goes into B layout once for all row blocks
 #pragma unroll
             for (int j = 0; j < kCols; ++j) {
-                uint32_t bj[4];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    // one byte permute: the low (j even) or high (j odd) halves of the two keys' registers
-                    const uint32_t v0 = (uint32_t)vr[2 * x][j >> 1], v1 = (uint32_t)vr[2 * x + 1][j >> 1];
-                    bj[x] = __builtin_amdgcn_perm(v1, v0, (j & 1) ? 0x07060302u : 0x05040100u);
-                }
-                const bf16x8 vbj = __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
+                const bf16x8 vbj = v_operand(vr, j);
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb)
                     acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi[rb], vbj, acc[rb][j], 0, 0, 0);
@@ -427,26 +473,27 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // then V tile), so the compiler's wait counts are exact: waiting for K leaves V in flight and
     // waiting for V leaves the next K in flight.
     row_t kr[8], vr[8];
+    v4i ka[2][kSteps];
     const int n_steady = n_full > 0 ? n_full - 1 : 0;   // full tiles whose successor is a full tile too
     int it = 0;
     if (n_steady > 0) {
-        issue_k_full(kr, 0);
+        if constexpr (kDirectK) issue_kd_full(ka, 0); else issue_k_full(kr, 0);
         // the K loads must be the older ones, as on every later step: without the barrier the
         // scheduler is free to issue V first, and the wait counts of the whole loop follow the entry
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (MODE != kEnergy) issue_v_full(vr, 0);
         finish_q();
         for (; it < n_steady; ++it) {
-            if (front(std::false_type{}, kr, it)) raise();
+            if (front(std::false_type{}, kr, ka, it)) raise();
             back(std::false_type{}, vr, it);
         }
     } else {
-        issue_k(kr, 0);
+        if constexpr (kDirectK) issue_kd(ka, 0); else issue_k(kr, 0);
         if constexpr (MODE != kEnergy) issue_v(vr, 0);
         finish_q();
     }
     for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
-        if (front(std::true_type{}, kr, it)) raise();
+        if (front(std::true_type{}, kr, ka, it)) raise();
         back(std::true_type{}, vr, it);
     }
 
@@ -470,9 +517,11 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         lw[rb] = rows_sum(l_run[rb]);                       // the normaliser is spread over the 4 row groups
+        float m_true = rows_max(m_top[rb]);                 // so is the largest score; to log2 units
+        m_true = m_true == ninf ? ninf : m_true * cs;       // (-inf stays -inf also when the scale is 0)
         if (r == 0) {
             st.m[w][16 * rb + c] = m_run[rb];
-            st.t[w][16 * rb + c] = m_true[rb];
+            st.t[w][16 * rb + c] = m_true;
             st.l[w][16 * rb + c] = lw[rb];
         }
     }
