@@ -89,6 +89,12 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // against 89-91 us at 64), but each cache line is requested twice; with one row block, where HBM
     // is the bound, it measured 0.6 us slower at 128k keys, so the staged form stays there.
     constexpr bool kDirectK = NRB == 4;
+    // With four row blocks a lane needs more than 256 registers, and the compiler then gives EVERY
+    // MFMA its result in accumulation registers, which the vector ALU cannot address: each score
+    // would cost a v_accvgpr_read (8 cycles per instruction, 32 per step).  The numerators belong
+    // there, the scores do not: their MFMAs are written as inline assembly with vector-register
+    // results (130 against 135 us per launch at 128 rows, 220.5 against 223.5 at 256).
+    constexpr bool kScoresInVgprs = NRB == 4;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -315,16 +321,67 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                 else af[G][t] = *reinterpret_cast<const v4i *>(stage + (16 * G + c) * kPitch + (4 * t + r) * 16);
             }
         f32x4 s[NRB][2];
+        if constexpr (!kScoresInVgprs) {
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) s[rb][0] = s[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int rb = 0; rb < NRB; ++rb) s[rb][0] = s[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < kSteps; ++t)
+            for (int t = 0; t < kSteps; ++t)
 #pragma unroll
-            for (int G = 0; G < 2; ++G)
+                for (int G = 0; G < 2; ++G)
 #pragma unroll
-                for (int rb = 0; rb < NRB; ++rb)
-                    s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[G][t]), qb[rb][t],
-                                                                        s[rb][G], 0, 0, 0);
+                    for (int rb = 0; rb < NRB; ++rb)
+                        s[rb][G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[G][t]), qb[rb][t],
+                                                                            s[rb][G], 0, 0, 0);
+        } else {
+            // Same MFMAs, two row blocks per statement, written out so that S lands in vector
+            // registers (see kScoresInVgprs).  Four independent chains per statement, k-step
+            // outermost; operands: %0-%3 = S[rb][G] of the two row blocks, then the A operands
+            // af[G][t], then the two row blocks' q[t].  The compiler does not see inside: the
+            // trailing s_nop covers the wait the vector ALU needs before it may read an MFMA
+            // result (8 wait states for this instruction; every earlier result is older).
+#pragma unroll
+            for (int rb = 0; rb < NRB; rb += 2) {
+                if constexpr (kSteps == 4) {
+                    asm volatile(
+                        "v_mfma_f32_16x16x32_bf16 %0, %4, %12, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %4, %16, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %8, %12, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %8, %16, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %0, %5, %13, %0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %5, %17, %2\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %9, %13, %1\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %9, %17, %3\n"
+                        "v_mfma_f32_16x16x32_bf16 %0, %6, %14, %0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %6, %18, %2\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %10, %14, %1\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %10, %18, %3\n"
+                        "v_mfma_f32_16x16x32_bf16 %0, %7, %15, %0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %7, %19, %2\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %11, %15, %1\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %11, %19, %3\n"
+                        "s_nop 15\n"
+                        : "=&v"(s[rb][0]), "=&v"(s[rb][1]), "=&v"(s[rb + 1][0]), "=&v"(s[rb + 1][1])
+                        : "v"(af[0][0]), "v"(af[0][1]), "v"(af[0][2]), "v"(af[0][3]),
+                          "v"(af[1][0]), "v"(af[1][1]), "v"(af[1][2]), "v"(af[1][3]),
+                          "v"(qb[rb][0]), "v"(qb[rb][1]), "v"(qb[rb][2]), "v"(qb[rb][3]),
+                          "v"(qb[rb + 1][0]), "v"(qb[rb + 1][1]), "v"(qb[rb + 1][2]), "v"(qb[rb + 1][3]));
+                } else {
+                    asm volatile(
+                        "v_mfma_f32_16x16x32_bf16 %0, %4, %8, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %4, %10, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %6, %8, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %6, %10, 0\n"
+                        "v_mfma_f32_16x16x32_bf16 %0, %5, %9, %0\n"
+                        "v_mfma_f32_16x16x32_bf16 %2, %5, %11, %2\n"
+                        "v_mfma_f32_16x16x32_bf16 %1, %7, %9, %1\n"
+                        "v_mfma_f32_16x16x32_bf16 %3, %7, %11, %3\n"
+                        "s_nop 15\n"
+                        : "=&v"(s[rb][0]), "=&v"(s[rb][1]), "=&v"(s[rb + 1][0]), "=&v"(s[rb + 1][1])
+                        : "v"(af[0][0]), "v"(af[0][1]), "v"(af[1][0]), "v"(af[1][1]),
+                          "v"(qb[rb][0]), "v"(qb[rb][1]), "v"(qb[rb + 1][0]), "v"(qb[rb + 1][1]));
+                }
+            }
+        }
         if constexpr (kDirectK) {   // the MFMAs above have read the tile: request the next one
             if constexpr (!masked) issue_kd_full(ka, it + 1);
             else if (it + 1 < n_iters) issue_kd(ka, it + 1);
@@ -425,6 +482,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 ph[x] = pack_bf16_rne(p[2 * x], p[2 * x + 1]);
+                // opaque to the optimiser, which otherwise converts p[2x] a second time to get the
+                // low half on its own
+                asm volatile("" : "+v"(ph[x]));
                 const float h0 = __uint_as_float(ph[x] << 16), h1 = __uint_as_float(ph[x] & 0xffff0000u);
                 pl[x] = pack_bf16_rne(p[2 * x] - h0, p[2 * x + 1] - h1);
             }
