@@ -363,8 +363,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                         : "=&v"(s[rb][0]), "=&v"(s[rb][1]), "=&v"(s[rb + 1][0]), "=&v"(s[rb + 1][1])
                         : "v"(af[0][0]), "v"(af[0][1]), "v"(af[0][2]), "v"(af[0][3]),
                           "v"(af[1][0]), "v"(af[1][1]), "v"(af[1][2]), "v"(af[1][3]),
-                          "v"(qb[rb][0]), "v"(qb[rb][1]), "v"(qb[rb][2]), "v"(qb[rb][3]),
-                          "v"(qb[rb + 1][0]), "v"(qb[rb + 1][1]), "v"(qb[rb + 1][2]), "v"(qb[rb + 1][3]));
+                          "a"(qb[rb][0]), "a"(qb[rb][1]), "a"(qb[rb][2]), "a"(qb[rb][3]),
+                          "a"(qb[rb + 1][0]), "a"(qb[rb + 1][1]), "a"(qb[rb + 1][2]), "a"(qb[rb + 1][3]));
                 } else {
                     asm volatile(
                         "v_mfma_f32_16x16x32_bf16 %0, %4, %8, 0\n"
@@ -378,7 +378,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                         "s_nop 15\n"
                         : "=&v"(s[rb][0]), "=&v"(s[rb][1]), "=&v"(s[rb + 1][0]), "=&v"(s[rb + 1][1])
                         : "v"(af[0][0]), "v"(af[0][1]), "v"(af[1][0]), "v"(af[1][1]),
-                          "v"(qb[rb][0]), "v"(qb[rb][1]), "v"(qb[rb + 1][0]), "v"(qb[rb + 1][1]));
+                          "a"(qb[rb][0]), "a"(qb[rb][1]), "a"(qb[rb + 1][0]), "a"(qb[rb + 1][1]));
                 }
             }
         }
@@ -526,35 +526,176 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
     };
 
+    // ---- Four row blocks: the steady step as an explicit software pipeline.
+    // At 64 rows per wave the SIMD's issue slots are the bound, a 16x16x32 MFMA keeps the matrix pipe
+    // busy for 16 cycles, and independent vector instructions of the same wave can use part of
+    // them -- but only if the program order offers some: the compiler's order is "all vector work,
+    // then all MFMAs".  The step is therefore written as a sequence of SLOTS, one MFMA plus two to
+    // four vector instructions each, pinned by scheduling barriers, and the loop is rotated so that
+    // independent work exists: step `it` of the loop runs
+    //     slots 0-31    S(it + 1) = K Q^T, all row blocks (into a second set of score registers)
+    //                   under the V tile's interleave and the first row block's exponentials / P split
+    //     slots 32-79   PV of row block rb under the exponentials / P split of row block rb + 1 and the
+    //                   lane maxima of S(it + 1)
+    //     slots 80-95   PV of the last row block under the move of S(it + 1) into the score registers
+    // and returns what maxima(it + 1) would: the caller raises shifts before the next step.  The
+    // score MFMAs are single inline-assembly statements here (vector-register results, q from
+    // accumulation registers); nothing reads a result sooner than 16 slots after its MFMA, far
+    // beyond the 8 wait states the vector ALU needs.
+    // (Not in the balanced kernel, which also keeps its walk over the share table in registers and
+    // would spill.)
+    constexpr bool kPipelined = NRB == 4 && MODE != kEnergy && !BALANCED;
+    auto pipelined_step = [&](row_t (&vr)[8], v4i (&ka)[2][kSteps], int it) -> bool {
+        constexpr int kQK = 2 * kSteps * NRB;   // score MFMAs of a step
+        constexpr int kPV = 2 * kCols;          // PV MFMAs of one row block
+        f32x4 sn[NRB][2];                       // S(it + 1)
+        uint32_t hi[NRB][4], lo[NRB][4];        // P = hi + lo as MFMA A operands
+        float pn[8], h0[4], h1[4];              // the row block whose P is being made
+        bool any_up = false;
+        // slice k = 0..15 of one row block's exponentials and P split: three vector instructions
+        auto p_slice = [&](int rb, int k) {
+            if (k < 8) {
+                pn[k] = exp2_hw(fmaf(sv[rb][k], cs, -m_run[rb]));
+                l_run[rb] += pn[k];
+            } else {
+                const int x = (k - 8) >> 1;
+                if (((k - 8) & 1) == 0) {
+                    hi[rb][x] = pack_bf16_rne(pn[2 * x], pn[2 * x + 1]);
+                    asm volatile("" : "+v"(hi[rb][x]));   // converted once (see make_p)
+                    h0[x] = __uint_as_float(hi[rb][x] << 16);
+                    h1[x] = __uint_as_float(hi[rb][x] & 0xffff0000u);
+                } else {
+                    lo[rb][x] = pack_bf16_rne(pn[2 * x] - h0[x], pn[2 * x + 1] - h1[x]);
+                }
+            }
+        };
+        // lane maximum of row block rb in S(it + 1), as maxima() takes it
+        auto next_max = [&](int rb) {
+            if constexpr (MODE != kGradient) {
+                float top = sn[rb][0][0];
+#pragma unroll
+                for (int e = 1; e < 8; ++e) top = fmaxf(top, sn[rb][e >> 2][e & 3]);
+                m8[rb] = top;
+                m_top[rb] = fmaxf(m_top[rb], top);
+                any_up |= top > thr[rb];
+            }
+        };
+        auto operand = [&](const uint32_t (&x)[4]) {
+            return __builtin_bit_cast(bf16x8, v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]});
+        };
+        // the vector work of slots 0 .. kQK - 1: kCols interleaves, then the 16 slices of row block 0
+        bf16x8 vb[kCols];
+        auto first_items = [&](int item) {
+            if (item < kCols) vb[item] = v_operand(vr, item);
+            else p_slice(0, item - kCols);
+        };
+        constexpr int kFirstItems = kCols + 16;
+
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- slots 0 .. kQK - 1: eight independent chains (row block, key group), k-step outermost
+#pragma unroll
+        for (int t = 0; t < kSteps; ++t)
+#pragma unroll
+            for (int G = 0; G < 2; ++G)
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) {
+                    const int i = (t * 2 + G) * NRB + rb;
+                    if (t == 0)
+                        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(sn[rb][G]) : "v"(ka[G][t]), "a"(qb[rb][t]));
+                    else
+                        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(sn[rb][G]) : "v"(ka[G][t]), "a"(qb[rb][t]));
+#pragma unroll
+                    for (int item = i * kFirstItems / kQK; item < (i + 1) * kFirstItems / kQK; ++item) first_items(item);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        // both tiles have been consumed: request the next ones, K first (the order the loop is entered with)
+        issue_kd_full(ka, it + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_v_full(vr, it + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- PV of row block rb
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            const bf16x8 a_hi = operand(hi[rb]), a_lo = operand(lo[rb]);
+#pragma unroll
+            for (int i = 0; i < kPV; ++i) {
+                const int j = i % kCols;
+                acc[rb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(i < kCols ? a_hi : a_lo, vb[j], acc[rb][j], 0, 0, 0);
+                if (rb + 1 < NRB) {
+#pragma unroll
+                    for (int k = i * 16 / kPV; k < (i + 1) * 16 / kPV; ++k) p_slice(rb + 1, k);
+                    // lane maxima of S(it + 1): two row blocks under PV(1), two under PV(2)
+                    if (rb >= 1 && (i == kPV / 4 || i == 3 * kPV / 4)) next_max(2 * (rb - 1) + (i > kPV / 2));
+                } else {
+                    // S(it + 1) becomes the current scores: row block i / (kPV / NRB), its share of the 8 values
+                    constexpr int kPer = kPV / NRB;            // slots per row block: 4 or 2
+                    const int mb = i / kPer, part = i % kPer;
+#pragma unroll
+                    for (int e = part * 8 / kPer; e < (part + 1) * 8 / kPer; ++e) sv[mb][e] = sn[mb][e >> 2][e & 3];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if constexpr (MODE != kGradient) return __builtin_amdgcn_ballot_w64(any_up) != 0;
+        return false;
+    };
+
     // One register tile of K and one of V per wave, refilled with the next step as soon as it has
-    // been consumed (a second V tile, requested a whole step ahead, measured no faster at 128k keys
-    // and 2.6 % slower at 1M: the stream is DRAM-bound, not latency-bound).  The steady-state loop is
-    // entered with exactly the pattern of outstanding loads it leaves behind on every step (K tile,
-    // then V tile), so the compiler's wait counts are exact: waiting for K leaves V in flight and
-    // waiting for V leaves the next K in flight.
+    // been consumed.  (More tiles in flight do not help.  One row block: a second V tile requested a
+    // whole step ahead measured no faster at 128k keys and 2.6 % slower at 1M, the stream is
+    // DRAM-bound.  Four row blocks: two K and two V tiles in flight, 232 against 235 us per launch
+    // at 256 rows.)  The steady-state loop is entered with exactly the pattern of outstanding loads
+    // it leaves behind on every step (K tile, then V tile), so the compiler's wait counts are exact.
     row_t kr[8], vr[8];
     v4i ka[2][kSteps];
-    const int n_steady = n_full > 0 ? n_full - 1 : 0;   // full tiles whose successor is a full tile too
     int it = 0;
-    if (n_steady > 0) {
-        if constexpr (kDirectK) issue_kd_full(ka, 0); else issue_k_full(kr, 0);
-        // the K loads must be the older ones, as on every later step: without the barrier the
-        // scheduler is free to issue V first, and the wait counts of the whole loop follow the entry
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (MODE != kEnergy) issue_v_full(vr, 0);
-        finish_q();
-        for (; it < n_steady; ++it) {
-            if (front(std::false_type{}, kr, ka, it)) raise();
-            back(std::false_type{}, vr, it);
+    if constexpr (!kPipelined) {
+        const int n_steady = n_full > 0 ? n_full - 1 : 0;   // full tiles whose successor is a full tile too
+        if (n_steady > 0) {
+            if constexpr (kDirectK) issue_kd_full(ka, 0); else issue_k_full(kr, 0);
+            // the K loads must be the older ones, as on every later step: without the barrier the
+            // scheduler is free to issue V first, and the wait counts of the whole loop follow the entry
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (MODE != kEnergy) issue_v_full(vr, 0);
+            finish_q();
+            for (; it < n_steady; ++it) {
+                if (front(std::false_type{}, kr, ka, it)) raise();
+                back(std::false_type{}, vr, it);
+            }
+        } else {
+            if constexpr (kDirectK) issue_kd(ka, 0); else issue_k(kr, 0);
+            if constexpr (MODE != kEnergy) issue_v(vr, 0);
+            finish_q();
+        }
+        for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
+            if (front(std::true_type{}, kr, ka, it)) raise();
+            back(std::true_type{}, vr, it);
         }
     } else {
-        if constexpr (kDirectK) issue_kd(ka, 0); else issue_k(kr, 0);
-        if constexpr (MODE != kEnergy) issue_v(vr, 0);
-        finish_q();
-    }
-    for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
-        if (front(std::true_type{}, kr, ka, it)) raise();
-        back(std::true_type{}, vr, it);
+        // rotated: the scores and maxima of a step are made during the step before
+        const int n_steady = n_full > 2 ? n_full - 2 : 0;   // full tiles whose two successors are full tiles too
+        bool pending;                                        // must a shift move before back(it)?
+        if (n_steady > 0) {
+            issue_kd_full(ka, 0);
+            finish_q();
+            pending = front(std::false_type{}, kr, ka, 0);   // S(0); leaves the K tile of step 1 in flight
+            __builtin_amdgcn_sched_barrier(0);
+            issue_v_full(vr, 0);
+            for (; it < n_steady; ++it) {
+                if (pending) raise();
+                pending = pipelined_step(vr, ka, it);
+            }
+        } else {
+            issue_kd(ka, 0);
+            issue_v(vr, 0);
+            finish_q();
+            pending = front(std::true_type{}, kr, ka, 0);
+        }
+        for (; it < n_iters; ++it) {   // last full tiles, ragged tail, causal limits
+            if (pending) raise();
+            back(std::true_type{}, vr, it);
+            if (it + 1 < n_iters) pending = front(std::true_type{}, kr, ka, it + 1);
+        }
     }
 
     // ---- merge the four waves (each holds every row over its own keys) through LDS as a
