@@ -944,3 +944,17 @@ def test_very_large_ragged_batch_falls_back_to_chunks():
     g = torch.Generator().manual_seed(9)
     w.valid_len = torch.randint(0, 97, (B,), generator=g, dtype=torch.int32).cuda()
     check(w)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("N", [140, 270, 400, 530, 655, 790, 915, 1045])
+def test_multi_token_four_row_blocks_every_length_of_the_steady_loop(N, d):
+    """64 (token, head) rows per kv head: the kernel whose steady steps are a hand-scheduled
+    software pipeline entered through a rotated loop.  With 128 keys per workgroup step these
+    lengths give 0 to 7 full tiles visible to every row, i.e. every number of pipelined steps from
+    none to five, each followed by the masked tail."""
+    w = W.make_multi(1, 16, 4, 1, d, N, torch.bfloat16, seed=5100 + N + d, device="cuda")
+    check_multi(w)
+    w2 = W.make_multi(2, 8, 16, 2, d, N, torch.bfloat16, seed=5200 + N + d, device="cuda")
+    w2.valid_len = torch.tensor([N, N - 37], dtype=torch.int32, device="cuda")
+    check_multi(w2)
