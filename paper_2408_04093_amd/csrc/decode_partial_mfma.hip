@@ -52,7 +52,6 @@ namespace {
 constexpr int waves_per_simd(int nrb, bool balanced) { return balanced ? (nrb == 1 ? 2 : 1) : (nrb <= 2 ? 2 : 1); }
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kMaxHeads = 16;
 
 // NRB is the number of 16-row blocks of (query token, head) pairs that share the
 // K tile in LDS and the V registers: 16 * NRB rows ride on one pass over K/V.
@@ -707,7 +706,6 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // lines to its own registers and stores the result: whole rows, a lane's kCols adjacent columns
     // at a time (16 lanes cover a row).  Two barriers, 3/4 of the numerators written and read once,
     // all of it 128-bit wide.
-    constexpr int kRows = 16 * NRB;
     constexpr int kUnitsPerBlock = kWaves / NRB;           // row groups per row block: 4, 2, 1
     constexpr int IW = 4 / kUnitsPerBlock;                  // rows of a lane per unit: 1, 2, 4
     constexpr int kVec = IW * kCols / 4;                    // IW rows x kCols columns = kVec 128-bit lines per lane and unit
