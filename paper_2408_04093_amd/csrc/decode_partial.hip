@@ -8,11 +8,16 @@
 // by the max shift of Appendix F.
 //
 // Data movement (the whole cost: the kernel is HBM-bound)
-//   * A K or V row is D fp32 = 256 or 512 bytes.  LPR = row_bytes/16 lanes
-//     each fetch 16 bytes of it with one 128-bit buffer load, so a wave-wide
-//     load covers RPW = 64/LPR complete rows, fully coalesced.
-//   * Every lane therefore owns EPL = 4 fixed columns of
-//     the head dimension and one of RPW interleaved "row groups" of keys.
+//   * A K or V row is D fp32 = 256 or 512 bytes.  A lane owns EPL = 8 (up to 4
+//     heads per workgroup) or 4 columns of the head dimension: LPR = D/EPL lanes
+//     share a row and fetch it with EPL/4 128-bit buffer loads, load j covering
+//     bytes [16 LPR j, 16 LPR (j+1)) of the row, so every load instruction reads
+//     RPW = 64/LPR contiguous pieces of 128-512 bytes.  Wider lanes mean fewer
+//     lanes per row: the cross-lane sum of a score takes log2(LPR) steps and the
+//     exponential of a score is evaluated by LPR lanes, and both are what this
+//     kernel spends its time on (EPL = 4 -> 8 at d = 128: 9.5 -> 5 vector
+//     instructions per key and head for the score).
+//   * Each lane belongs to one of RPW interleaved "row groups" of keys.
 //     Each row group runs its own online softmax; they are merged at the end.
 //   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
 //     while it computes the current one (register double buffering), so with
@@ -38,7 +43,7 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kKeysPerStep = 4;   // keys per row group per pipeline step
+constexpr int kLoadsPerStep = 4;  // 128-bit loads per lane, stream and pipeline step (keys x loads per key)
 constexpr int kAux = 2;           // cache-policy bits of the K/V buffer loads: 2 = non-temporal.  K/V are
                                   // read once; streaming them non-temporally measured 7.0 TB/s against
                                   // 6.2 TB/s for default-policy loads on a read-only probe.
@@ -46,31 +51,34 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 
 constexpr int kBytes = 4;   // fp32 K/V
-constexpr int EPL = 4;      // columns per lane: one 128-bit load
 using acc_t = double;       // score / running-max type
+// columns per lane: two 128-bit loads per row, one when 8 heads share the workgroup (q alone would
+// take 128 registers otherwise)
+constexpr int columns_per_lane(int gt) { return gt <= 4 ? 8 : 4; }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
     // raw buffer (stride 0): hardware returns 0 for any access past `bytes`
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 
-// partial dot product of this lane's 16 bytes of a key row with q (q widened once to fp64)
-__device__ __forceinline__ double lane_dot(const v4i &k, const double (&q)[4]) {
+// partial dot product of this lane's columns of a key row with q (q widened once to fp64)
+template <int EPL>
+__device__ __forceinline__ double lane_dot(const v4i (&k)[EPL / 4], const double (&q)[EPL]) {
     double acc = 0.0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) acc = fma((double)__int_as_float(k[r]), q[r], acc);
+    for (int e = 0; e < EPL; ++e) acc = fma((double)__int_as_float(k[e >> 2][e & 3]), q[e], acc);
     return acc;
 }
 
 enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 
-template <int U>
+template <int U, int EPL>
 struct Tile {
-    v4i k[U];
-    v4i v[U];
+    v4i k[U][EPL / 4];
+    v4i v[U][EPL / 4];
 };
 
-template <int GT>
+template <int GT, int EPL>
 struct State {
     acc_t m[GT];        // running max, log2 units
     float l[GT];        // running normaliser
@@ -82,9 +90,9 @@ __device__ __forceinline__ acc_t neg_inf() { return -__builtin_huge_val(); }
 // One pipeline step: U keys per row group, GT heads.
 //   row0: chunk-relative index of this lane's first key (u = 0); key u is
 //   row0 + u*RPW.  MASKED steps treat rows >= n as absent.
-template <int D, int GT, int U, bool MASKED, int MODE>
-__device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4], State<GT> &st, acc_t c, int row0,
-                                     int n) {
+template <int D, int GT, int U, int EPL, bool MASKED, int MODE>
+__device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT][EPL], State<GT, EPL> &st, acc_t c,
+                                     int row0, int n) {
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
 
     acc_t s2[U][GT];
@@ -92,7 +100,7 @@ __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4],
     for (int u = 0; u < U; ++u) {
 #pragma unroll
         for (int h = 0; h < GT; ++h) {
-            acc_t acc = group_sum<LPR>(lane_dot(T.k[u], q[h]));
+            acc_t acc = group_sum<LPR>(lane_dot<EPL>(T.k[u], q[h]));
             s2[u][h] = acc * c;
             if constexpr (MASKED)
                 if (row0 + u * RPW >= n) s2[u][h] = neg_inf();
@@ -129,7 +137,7 @@ __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4],
     for (int u = 0; u < U; ++u) {
         float vf[EPL];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) vf[e] = MODE != kEnergy ? __int_as_float(T.v[u][e]) : 0.f;
+        for (int e = 0; e < EPL; ++e) vf[e] = MODE != kEnergy ? __int_as_float(T.v[u][e >> 2][e & 3]) : 0.f;
 #pragma unroll
         for (int h = 0; h < GT; ++h) {
             float p = exp2_hw((float)(s2[u][h] - st.m[h]));
@@ -144,8 +152,10 @@ __device__ __forceinline__ void step(const Tile<U> &T, const double (&q)[GT][4],
     }
 }
 
-template <int D, int GT, int U, int MODE>
+template <int D, int GT, int MODE>
 __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
+    constexpr int EPL = columns_per_lane(GT), NL = EPL / 4;   // columns and 128-bit loads per lane and row
+    constexpr int U = NL == 2 ? 1 : kLoadsPerStep / NL;                     // keys per row group per pipeline step
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
     constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
 
@@ -177,14 +187,18 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         return;
     }
 
-    // q: this lane's EPL columns of each head, kept in registers
-    double q[GT][4];
+    // q: this lane's EPL columns of each head, kept in registers.  Element e = 4 j + r of a lane is
+    // column 4 (j LPR + sub) + r: load j of a row, this lane's 16 bytes of it.
+    double q[GT][EPL];
 #pragma unroll
     for (int h = 0; h < GT; ++h) {
-        const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + sub * EPL) * kBytes;
-        const v4i raw = *reinterpret_cast<const v4i *>(qp);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) q[h][r] = (double)__int_as_float(raw[r]);
+        for (int j = 0; j < NL; ++j) {
+            const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + 4 * (j * LPR + sub)) * kBytes;
+            const v4i raw = *reinterpret_cast<const v4i *>(qp);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) q[h][4 * j + r] = (double)__int_as_float(raw[r]);
+        }
     }
 
     const char *kb = (const char *)a.K + ((int64_t)b * a.k_sb + (int64_t)hk * a.k_sh) * kBytes +
@@ -205,17 +219,21 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         voff[u] = (uint32_t)(row_lane + u * RPW) * a.v_row_bytes + sub * 16;
     }
 
-    auto issue = [&](Tile<U> &T, int it) {
+    auto issue = [&](Tile<U, EPL> &T, int it) {
         if (it < n_full) {
             const uint32_t kinc = (uint32_t)it * ROWS_ITER * a.k_row_bytes;
             const uint32_t vinc = (uint32_t)it * ROWS_ITER * a.v_row_bytes;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc), 0, kAux);
+#pragma unroll
+                for (int j = 0; j < NL; ++j)
+                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc + j * LPR * 16), 0, kAux);
             if constexpr (MODE != kEnergy) {
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc), 0, kAux);
+#pragma unroll
+                    for (int j = 0; j < NL; ++j)
+                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc + j * LPR * 16), 0, kAux);
             }
         } else {
             // ragged last step: rows past the chunk are redirected to its last
@@ -228,16 +246,20 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                T.k[u] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + sub * 16), 0, kAux);
+#pragma unroll
+                for (int j = 0; j < NL; ++j)
+                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + (j * LPR + sub) * 16), 0, kAux);
             if constexpr (MODE != kEnergy) {
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    T.v[u] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + sub * 16), 0, kAux);
+#pragma unroll
+                    for (int j = 0; j < NL; ++j)
+                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + (j * LPR + sub) * 16), 0, kAux);
             }
         }
     };
 
-    State<GT> st;
+    State<GT, EPL> st;
 #pragma unroll
     for (int h = 0; h < GT; ++h) {
         st.m[h] = neg_inf();
@@ -253,15 +275,15 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     }
     const acc_t c = (acc_t)a.c;
 
-    auto compute = [&](const Tile<U> &T, int it) {
+    auto compute = [&](const Tile<U, EPL> &T, int it) {
         const int row0 = it * ROWS_ITER + row_lane;
-        if (it < n_full) step<D, GT, U, false, MODE>(T, q, st, c, row0, n);
-        else step<D, GT, U, true, MODE>(T, q, st, c, row0, n);
+        if (it < n_full) step<D, GT, U, EPL, false, MODE>(T, q, st, c, row0, n);
+        else step<D, GT, U, EPL, true, MODE>(T, q, st, c, row0, n);
     };
 
     // two register tiles, ping-pong: the loads of step it+1 are in flight
     // while step it is computed
-    Tile<U> ta, tb;
+    Tile<U, EPL> ta, tb;
     issue(ta, 0);
     for (int it = 0; it < n_iters; it += 2) {
         if (it + 1 < n_iters) issue(tb, it + 1);
@@ -290,7 +312,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 #pragma unroll
         for (int h = 0; h < GT; ++h)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) lds_o[w][h][sub * EPL + e] = st.o[h][e];
+            for (int e = 0; e < EPL; ++e) lds_o[w][h][4 * ((e >> 2) * LPR + sub) + (e & 3)] = st.o[h][e];
     }
     if (lane == 0) {
 #pragma unroll
@@ -335,12 +357,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
 template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, int mode, hipStream_t s) {
-    constexpr int U = kKeysPerStep;
     const dim3 grid((uint32_t)launch_blocks(a));
     switch (mode) {
-        case kEnergy: return launch_kernel(decode_partial_kernel<D, GT, U, kEnergy>, grid, dim3(kThreads), s, a);
-        case kGradient: return launch_kernel(decode_partial_kernel<D, GT, U, kGradient>, grid, dim3(kThreads), s, a);
-        default: return launch_kernel(decode_partial_kernel<D, GT, U, kFull>, grid, dim3(kThreads), s, a);
+        case kEnergy: return launch_kernel(decode_partial_kernel<D, GT, kEnergy>, grid, dim3(kThreads), s, a);
+        case kGradient: return launch_kernel(decode_partial_kernel<D, GT, kGradient>, grid, dim3(kThreads), s, a);
+        default: return launch_kernel(decode_partial_kernel<D, GT, kFull>, grid, dim3(kThreads), s, a);
     }
 }
 
@@ -349,7 +370,7 @@ template <int D, int GT>
 int occupancy_one() {
     static const int cached = [] {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kKeysPerStep, kFull>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kFull>, kThreads, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
