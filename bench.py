@@ -29,6 +29,7 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 on the matrix cores, published
 LLC_BYTES = 256 << 20      # Infinity Cache
 SETTLE_MS = 20             # untimed steps before the W warm-up steps (clock settling)
+IDLE_MS_AFTER_SETUP = 2000 # idle time between building the inputs and the first step (see run_workload)
 KERNEL_SOURCES = ["decode_partial_mfma.hip", "mfma_tile.hpp", "chunking.hpp", "balanced_index.hpp",
                   "wave_ops.hpp", "ta_internal.hpp", "ta_api.cpp"]
 
@@ -195,8 +196,13 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"
         if rc:
             raise ta.TAError(rc, "ta_decode")
 
-    # engine clocks settle within a few milliseconds of sustained work: the setup above leaves the GPU idle
-    # (host-side bookkeeping), so some untimed steps run first, whatever W is, then the W warm-up steps
+    # Building the inputs is seconds of GPU work of its own (random fills, sorts), and so is whatever workload
+    # this process timed before: the chip then runs the next seconds at a lower engine clock (measured: the same
+    # workload 3-4 % slower right after another one than in a fresh process, and back to the fresh figure after
+    # two idle seconds).  So that every workload is timed from the same state, the GPU idles first; then the
+    # clocks are brought up again by untimed steps, whatever W is, then the W warm-up steps.
+    torch.cuda.synchronize()
+    time.sleep(IDLE_MS_AFTER_SETUP * 1e-3)
     t_settle = time.perf_counter()
     while time.perf_counter() - t_settle < SETTLE_MS * 1e-3:
         for i in range(8):
@@ -289,7 +295,7 @@ def run_workload(name, steps, warmup, cpu_baseline, use_graph=False, op="decode"
 
     result = {
         "metric": "decode_attention_hbm_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup, "settle_ms_before_warmup": SETTLE_MS,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "idle_ms_after_setup": IDLE_MS_AFTER_SETUP, "settle_ms_before_warmup": SETTLE_MS,
         "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
         "us_per_step_stats": step_stats,
         "pct_of_hbm_peak": round(100 * gbps / HBM_PEAK_GBPS, 2),
