@@ -48,7 +48,8 @@
  *     ta_tree_combine pass Sq*Hq as Hq.  All tokens and heads of a KV group
  *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 64; beyond that the
  *     (token, head) pairs of the group, taken token-major, are processed in
- *     slices of 64, each slice reading K/V once.  Sq > 1 needs bf16 inputs.
+ *     slices of 64, each slice reading K/V once (bf16 inputs; fp32 inputs take
+ *     the pairs in slices of up to 8).
  */
 #ifndef TREE_ATTN_H
 #define TREE_ATTN_H

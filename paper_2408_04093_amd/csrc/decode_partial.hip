@@ -1,5 +1,5 @@
 // decode_partial, vector-ALU form: per-chunk partial softmax statistics
-// (m, l, o) for one query token, all heads of a GQA group at once.  This kernel
+// (m, l, o), a few (query token, head) rows of a GQA group at once.  This kernel
 // serves fp32 K/V; bf16 runs on the matrix-core kernel in
 // decode_partial_mfma.hip.  Tree Attention (arXiv 2408.04093)
 // Algorithm 3 steps 1-2 with the chunks mapped to workgroups of one gfx950 GPU
@@ -22,8 +22,12 @@
 //   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
 //     while it computes the current one (register double buffering), so with
 //     8-16 resident waves a CU has tens of KB outstanding.
-//   * All GT query heads that share the KV head are scored against the same
-//     registers: every K/V byte is fetched once per group.
+//   * GT (query token, head-in-group) rows that share the KV head are scored
+//     against the same registers.  Rows are numbered token-major (token * g +
+//     head in group) and cut into slices of GT: with one query token and g <= 8
+//     every K/V byte is fetched once per group; several tokens (the causal
+//     energy of Appendix C.1 on the last Sq positions) take Sq g / GT passes,
+//     each row with its own causal limit.
 //
 // Pass modes (the paper's Algorithm 3 against its Algorithms 1 and 2), as on the matrix-core kernel:
 //   kFull (m, l, o) per chunk; kEnergy (m, l) only, K is the only stream; kGradient
@@ -89,10 +93,11 @@ __device__ __forceinline__ acc_t neg_inf() { return -__builtin_huge_val(); }
 
 // One pipeline step: U keys per row group, GT heads.
 //   row0: chunk-relative index of this lane's first key (u = 0); key u is
-//   row0 + u*RPW.  MASKED steps treat rows >= n as absent.
+//   row0 + u*RPW.  MASKED steps treat keys >= lim[h] as absent for row h (the end of the chunk, or
+//   the row's causal limit inside it).
 template <int D, int GT, int U, int EPL, bool MASKED, int MODE>
 __device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT][EPL], State<GT, EPL> &st, acc_t c,
-                                     int row0, int n) {
+                                     int row0, const int (&lim)[GT]) {
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
 
     acc_t s2[U][GT];
@@ -103,7 +108,7 @@ __device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT
             acc_t acc = group_sum<LPR>(lane_dot<EPL>(T.k[u], q[h]));
             s2[u][h] = acc * c;
             if constexpr (MASKED)
-                if (row0 + u * RPW >= n) s2[u][h] = neg_inf();
+                if (row0 + u * RPW >= lim[h]) s2[u][h] = neg_inf();
         }
     }
 
@@ -142,7 +147,7 @@ __device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT
         for (int h = 0; h < GT; ++h) {
             float p = exp2_hw((float)(s2[u][h] - st.m[h]));
             if constexpr (MASKED)
-                if (row0 + u * RPW >= n) p = 0.f;
+                if (row0 + u * RPW >= lim[h]) p = 0.f;
             st.l[h] += p;
             if constexpr (MODE != kEnergy) {
 #pragma unroll
@@ -168,23 +173,36 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     if (cr.surplus) return;
     const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
-    const int hq0 = hk * a.g + cr.slice * GT;
     const int64_t lo = cr.lo;
     const int n = cr.n;
 
-    const int64_t pidx0 = ((int64_t)b * a.Hq + hq0) * a.P + chunk;   // + h * P per head
+    // This workgroup's rows: (token, head in group) pairs cr.slice * GT + h of the kv head, numbered
+    // token-major.  vrow: index of a row in the [B, Sq, Hq] arrays (q, lse) and, times P, in the partials.
+    const int HqV = a.Sq * a.Hq;
+    auto token_of = [&](int h) { return (cr.slice * GT + h) / a.g; };
+    auto vrow = [&](int h) -> int64_t {
+        return (int64_t)b * HqV + (int64_t)token_of(h) * a.Hq + hk * a.g + (cr.slice * GT + h) % a.g;
+    };
+    auto pidx_of = [&](int h) -> int64_t { return vrow(h) * a.P + chunk; };
     if (n <= 0) {   // empty chunk: the identity of the merge
         if constexpr (MODE != kEnergy) {
-            for (int i = tid; i < GT * D; i += kThreads)
-                a.part_o[(pidx0 + (int64_t)(i / D) * a.P) * D + (i % D)] = 0.f;
+            for (int i = tid; i < GT * D; i += kThreads) a.part_o[pidx_of(i / D) * D + (i % D)] = 0.f;
         }
         if constexpr (MODE != kGradient) {
             if (tid < GT) {
-                a.part_m[pidx0 + (int64_t)tid * a.P] = -__builtin_huge_valf();
-                a.part_l[pidx0 + (int64_t)tid * a.P] = 0.f;
+                a.part_m[pidx_of(tid)] = -__builtin_huge_valf();
+                a.part_l[pidx_of(tid)] = 0.f;
             }
         }
         return;
+    }
+    // keys of the chunk each row may see: token t attends keys < L - Sq + 1 + t (chunk-relative,
+    // clamped to [0, n]); n for every row when there is one query token
+    int lim[GT];
+#pragma unroll
+    for (int h = 0; h < GT; ++h) {
+        const int64_t l = cr.L - a.Sq + 1 + token_of(h) - lo;
+        lim[h] = (int)(l < 0 ? 0 : (l > n ? n : l));
     }
 
     // q: this lane's EPL columns of each head, kept in registers.  Element e = 4 j + r of a lane is
@@ -194,7 +212,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     for (int h = 0; h < GT; ++h) {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const char *qp = (const char *)a.q + (((int64_t)b * a.Hq + hq0 + h) * D + 4 * (j * LPR + sub)) * kBytes;
+            const char *qp = (const char *)a.q + (vrow(h) * D + 4 * (j * LPR + sub)) * kBytes;
             const v4i raw = *reinterpret_cast<const v4i *>(qp);
 #pragma unroll
             for (int r = 0; r < 4; ++r) q[h][4 * j + r] = (double)__int_as_float(raw[r]);
@@ -209,7 +227,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vb, (uint32_t)(n - 1) * a.v_row_bytes + D * kBytes);
 
     const int n_iters = (n + ROWS_ITER - 1) / ROWS_ITER;
-    const int n_full = n / ROWS_ITER;
+    const int n_full = lim[0] / ROWS_ITER;   // steps whose keys every row sees (rows are token-major: row 0 sees least)
     const int row_lane = w * ROWS_WAVE + rg;   // + it*ROWS_ITER + u*RPW
 
     uint32_t koff[U], voff[U];   // byte offsets of this lane's loads in iteration 0
@@ -267,7 +285,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         if constexpr (MODE == kGradient) {
             // the shift is the given total logsumexp (natural log -> log2 units); a row with no key at
             // all (lse = -inf) gets +inf so that every exponential below is exactly 0
-            const float given = a.lse_in[(int64_t)b * a.Hq + hq0 + h];
+            const float given = a.lse_in[vrow(h)];
             st.m[h] = given == -__builtin_huge_valf() ? __builtin_huge_val() : (acc_t)given * (acc_t)kLog2e;
         }
 #pragma unroll
@@ -277,8 +295,8 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
 
     auto compute = [&](const Tile<U, EPL> &T, int it) {
         const int row0 = it * ROWS_ITER + row_lane;
-        if (it < n_full) step<D, GT, U, EPL, false, MODE>(T, q, st, c, row0, n);
-        else step<D, GT, U, EPL, true, MODE>(T, q, st, c, row0, n);
+        if (it < n_full) step<D, GT, U, EPL, false, MODE>(T, q, st, c, row0, lim);
+        else step<D, GT, U, EPL, true, MODE>(T, q, st, c, row0, lim);
     };
 
     // two register tiles, ping-pong: the loads of step it+1 are in flight
@@ -341,8 +359,9 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
         // consistent with the number a reader of part_m will see.
         const float m_nat = (float)(ms * (acc_t)kLn2);
         const acc_t resid = fma(-(acc_t)m_nat, (acc_t)kLog2e, ms);
-        const float fix = exp2_hw((float)resid);
-        const int64_t pidx = pidx0 + (int64_t)h * a.P;
+        // a row that sees no key of the chunk (causal limit) keeps ms = -inf, l = o = 0: the identity
+        const float fix = ms == neg_inf() ? 1.0f : exp2_hw((float)resid);
+        const int64_t pidx = pidx_of(h);
         if constexpr (MODE == kGradient) {
             a.part_o[pidx * D + col] = ot;   // weights were final all along: the shift is not stored
         } else {
@@ -396,7 +415,7 @@ int occupancy_one() {
 
 hipError_t launch_decode_partial(const PartialArgs &a, int dtype, int d, int mode, hipStream_t s) {
     if (dtype != TA_F32) return hipErrorInvalidValue;   // bf16 belongs to the matrix-core kernel
-    const int gt = a.g / a.slices;
+    const int gt = a.Sq * a.g / a.slices;   // (token, head) rows per workgroup
     TA_DISPATCH(launch_one, a, mode, s);
 }
 

@@ -26,7 +26,9 @@ inline int64_t launch_groups(const ta_problem *p) {
     if (use_mfma_path(p->qkv_dtype, p->d)) {
         return (int64_t)p->B * p->Hkv * ((total_rows(p) + kMaxRows - 1) / kMaxRows);
     }
-    return (int64_t)p->B * p->Hkv * (g / heads_per_workgroup(p->qkv_dtype, p->d, g));
+    // vector-ALU kernel: the (token, head-in-group) rows of a kv head, a few per workgroup
+    (void)g;
+    return (int64_t)p->B * p->Hkv * (total_rows(p) / heads_per_workgroup(p->qkv_dtype, p->d, (int)total_rows(p)));
 }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -52,7 +54,6 @@ ta_status check_problem(const ta_problem *p) {
     if (p->k_stride_n * eb >= ((int64_t)1 << 31) || p->v_stride_n * eb >= ((int64_t)1 << 31)) return TA_ERR_UNSUPPORTED;
     if (p->N >= ((int64_t)1 << 40)) return TA_ERR_UNSUPPORTED;
     if (p->Sq < 0 || p->Sq > 4096) return TA_ERR_SHAPE;
-    if (p->Sq > 1 && !use_mfma_path(p->qkv_dtype, p->d)) return TA_ERR_UNSUPPORTED;
     if ((int64_t)p->B * p->Hq * tokens(p) >= ((int64_t)1 << 28)) return TA_ERR_SHAPE;
     return TA_OK;
 }
@@ -99,7 +100,7 @@ int device_compute_units() {
 int32_t suggest_chunks(const ta_problem *p, int cus) {
     constexpr int64_t kMinChunk = 256;
     const int g = p->Hq / p->Hkv;
-    const int gt = heads_per_workgroup(p->qkv_dtype, p->d, g);
+    const int gt = heads_per_workgroup(p->qkv_dtype, p->d, use_mfma_path(p->qkv_dtype, p->d) ? g : (int)total_rows(p));
     const int64_t groups = launch_groups(p);
     int64_t P;
     if (use_mfma_path(p->qkv_dtype, p->d)) {

@@ -101,7 +101,6 @@ def test_workspace_and_chunk_heuristic(lib):
     (lambda p: setattr(p, "N", 1 << 41), 6),
     (lambda p: setattr(p, "k_stride_n", 1 << 31), 6),   # a row of 4 GiB
     (lambda p: setattr(p, "Sq", -1), 2),
-    (lambda p: (setattr(p, "Sq", 4), setattr(p, "qkv_dtype", 1)), 6),   # several tokens need bf16
 ])
 def test_bad_problems_are_refused_before_launch(lib, mutate, code):
     p = llama_problem()
@@ -146,9 +145,10 @@ def test_energy_and_two_pass_argument_checks(lib):
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, None, FAKE, need, FAKE, FAKE, None) == 1
     assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4   # checked before any launch
     assert ta.ta_decode(p, FAKE, FAKE, FAKE, FAKE, need, FAKE + 1, FAKE, None) == 4
-    p.qkv_dtype, p.Sq = ta.TA_F32, 2      # fp32 K/V: one query token per sequence only
-    assert ta.ta_energy(p, FAKE, FAKE, FAKE, 1 << 30, FAKE, None) == 6
-    assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, 1 << 30, FAKE, FAKE, None) == 6
+    p.qkv_dtype, p.Sq = ta.TA_F32, 2      # fp32 K/V takes several query tokens too: same checks
+    need = ta.ta_workspace_bytes(p, ta.ta_suggest_chunks(p))
+    assert ta.ta_energy(p, FAKE, FAKE, FAKE, need - 1, FAKE, None) == 5
+    assert ta.ta_decode_two_pass(p, FAKE, FAKE, FAKE, FAKE, need - 1, FAKE, FAKE, None) == 5
 
 
 def test_chunk_heuristic_invariants_on_seeded_random_problems(lib):
@@ -166,7 +166,7 @@ def test_chunk_heuristic_invariants_on_seeded_random_problems(lib):
         p.N = int(rng.choice([1, 255, 256, 257, 1000, 4096, 5000, 65536, 1 << 20]))
         bf16 = bool(rng.integers(0, 2))
         p.qkv_dtype = ta.TA_BF16 if bf16 else ta.TA_F32
-        p.Sq = int(rng.choice([0, 1, 3, 17])) if bf16 else 0
+        p.Sq = int(rng.choice([0, 1, 3, 17]))
         if p.N * p.d * (2 if bf16 else 4) >= 1 << 32:
             continue
         p.k_stride_n = p.v_stride_n = p.d
@@ -179,7 +179,7 @@ def test_chunk_heuristic_invariants_on_seeded_random_problems(lib):
         sq = max(1, p.Sq)
         assert ta.ta_workspace_bytes(p, P) >= p.B * sq * p.Hq * P * (p.d + 2) * 4
         assert ta.ta_workspace_bytes(p, P) % 256 == 0
-        slices = -(-sq * g // 64) if bf16 else 1
+        slices = -(-sq * g // 64) if bf16 else sq * g   # fp32: at least one (token, head) row per workgroup
         assert p.B * p.Hkv * slices * P < 1 << 31
 
 
