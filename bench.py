@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 on the matrix cores, published
 LLC_BYTES = 256 << 20      # Infinity Cache
 SETTLE_MS = 20             # untimed steps before the W warm-up steps (clock settling)
 IDLE_MS_AFTER_SETUP = 2000 # idle time between building the inputs and the first step (see run_workload)
-KERNEL_SOURCES = ["decode_partial_mfma.hip", "mfma_tile.hpp", "chunking.hpp", "balanced_index.hpp",
+KERNEL_SOURCES = ["decode_partial_mfma.hip", "mfma_tile.hpp", "chunking.hpp", "balanced_index.hpp", "balanced_walk.hpp",
                   "wave_ops.hpp", "ta_internal.hpp", "ta_api.cpp"]
 
 

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtree_attn.so")
 SOURCES = ["ta_api.cpp", "decode_partial.hip", "decode_partial_mfma.hip", "tree_combine.hip"]
-HEADERS = ["ta_internal.hpp", "wave_ops.hpp", "chunking.hpp", "mfma_tile.hpp", "balanced_index.hpp"]
+HEADERS = ["ta_internal.hpp", "wave_ops.hpp", "chunking.hpp", "mfma_tile.hpp", "balanced_index.hpp", "balanced_walk.hpp"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -27,6 +27,16 @@ struct ChunkRange {
     int n;        // number of keys (0 = empty)
 };
 
+// Where one range of keys of one (batch, kv head, row slice) goes: what a streaming kernel processes
+// in one go, a whole chunk (chunked launch) or one piece of a share (balanced launch).
+struct Range {
+    int b, hk, slice;
+    int64_t lo;     // first key
+    int n;          // number of keys
+    int64_t L;      // valid length of the sequence (causal limits among query tokens)
+    int64_t slot;   // chunked launch: chunk index; balanced launch: piece id
+};
+
 constexpr int kMaxRankedChunks = 256;
 
 __device__ __forceinline__ void clamp_bounds(const PartialArgs &a, int chunk, int64_t L, int64_t &lo, int64_t &hi) {

@@ -38,6 +38,7 @@
 //   |score| does not cost precision; exponentials and sums in fp32.
 //   Scores are kept in log2 units (score * scale * log2 e) so the exponential
 //   is the bare v_exp_f32; the partial is converted to natural units on store.
+#include "balanced_walk.hpp"
 #include "chunking.hpp"
 #include "ta_internal.hpp"
 #include "wave_ops.hpp"
@@ -157,8 +158,18 @@ __device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT
     }
 }
 
-template <int D, int GT, int MODE>
-__global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
+// LDS of a workgroup: the merge of its waves
+template <int D, int GT>
+struct MergeShared {
+    float o[kWaves][GT][D];
+    float l[kWaves][GT];
+    acc_t m[kWaves][GT];
+};
+
+// The whole streaming computation for one range of keys of one (batch, kv head, row slice): called
+// once per workgroup by the chunked kernel and once per piece by the balanced kernel.
+template <int D, int GT, int MODE, bool BALANCED>
+__device__ __forceinline__ void process_range(const PartialArgs &a, const Range &cr, MergeShared<D, GT> &lds) {
     constexpr int EPL = columns_per_lane(GT), NL = EPL / 4;   // columns and 128-bit loads per lane and row
     constexpr int U = NL == 2 ? 1 : kLoadsPerStep / NL;                     // keys per row group per pipeline step
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
@@ -169,10 +180,7 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int sub = lane % LPR, rg = lane / LPR;
 
-    __shared__ int sh_rank[kMaxRankedChunks + 1];
-    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
-    if (cr.surplus) return;
-    const int chunk = cr.chunk, hk = cr.hk, b = cr.b;
+    const int hk = cr.hk, b = cr.b;
     const int64_t lo = cr.lo;
     const int n = cr.n;
 
@@ -183,7 +191,11 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     auto vrow = [&](int h) -> int64_t {
         return (int64_t)b * HqV + (int64_t)token_of(h) * a.Hq + hk * a.g + (cr.slice * GT + h) % a.g;
     };
-    auto pidx_of = [&](int h) -> int64_t { return vrow(h) * a.P + chunk; };
+    // index of a row's partial: [B, Sq*Hq, P] in a chunked launch, [piece, piece_rows] in a balanced one
+    auto pidx_of = [&](int h) -> int64_t {
+        if constexpr (BALANCED) return cr.slot * a.piece_rows + h;
+        else return vrow(h) * a.P + cr.slot;
+    };
     if (n <= 0) {   // empty chunk: the identity of the merge
         if constexpr (MODE != kEnergy) {
             for (int i = tid; i < GT * D; i += kThreads) a.part_o[pidx_of(i / D) * D + (i % D)] = 0.f;
@@ -323,9 +335,9 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     }
 
     // ---- merge the waves of the workgroup through LDS
-    __shared__ float lds_o[kWaves][GT][D];
-    __shared__ float lds_l[kWaves][GT];
-    __shared__ acc_t lds_m[kWaves][GT];
+    auto &lds_o = lds.o;
+    auto &lds_l = lds.l;
+    auto &lds_m = lds.m;
     if (rg == 0) {
 #pragma unroll
         for (int h = 0; h < GT; ++h)
@@ -374,6 +386,26 @@ __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialA
     }
 }
 
+// Chunked launch: one workgroup per (batch, kv head, row slice, chunk).
+template <int D, int GT, int MODE>
+__global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
+    __shared__ MergeShared<D, GT> lds;
+    __shared__ int sh_rank[kMaxRankedChunks + 1];
+    const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
+    if (cr.surplus) return;
+    const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
+    process_range<D, GT, MODE, false>(a, rg, lds);
+}
+
+// Balanced launch for ragged batches: every workgroup walks its equal-cost share of all keys, piece
+// by piece (balanced_walk.hpp).
+template <int D, int GT, int MODE>
+__global__ void __launch_bounds__(kThreads) decode_balanced_kernel(const PartialArgs a) {
+    __shared__ MergeShared<D, GT> lds;
+    __shared__ BalancedShared walk;
+    balanced_walk<kThreads, kBytes * D>(a, walk, [&](const Range &rg) { process_range<D, GT, MODE, true>(a, rg, lds); });
+}
+
 template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, int mode, hipStream_t s) {
     const dim3 grid((uint32_t)launch_blocks(a));
@@ -393,6 +425,30 @@ int occupancy_one() {
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
             n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
+        }
+        return n;
+    }();
+    return cached;
+}
+
+template <int D, int GT>
+hipError_t launch_balanced_one(const PartialArgs &a, int mode, hipStream_t s) {
+    const dim3 grid((uint32_t)a.W);
+    switch (mode) {
+        case kEnergy: return launch_kernel(decode_balanced_kernel<D, GT, kEnergy>, grid, dim3(kThreads), s, a);
+        case kGradient: return launch_kernel(decode_balanced_kernel<D, GT, kGradient>, grid, dim3(kThreads), s, a);
+        default: return launch_kernel(decode_balanced_kernel<D, GT, kFull>, grid, dim3(kThreads), s, a);
+    }
+}
+
+template <int D, int GT>
+int balanced_occupancy_one() {
+    static const int cached = [] {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_balanced_kernel<D, GT, kFull>, kThreads, 0) !=
+                hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = 1;
         }
         return n;
     }();
@@ -423,5 +479,12 @@ int decode_partial_occupancy(int dtype, int d, int gt) {
     (void)dtype;
     TA_DISPATCH(occupancy_one);
 }
+
+hipError_t launch_decode_balanced(const PartialArgs &a, int d, int mode, hipStream_t s) {
+    const int gt = a.Sq * a.g / a.slices;
+    TA_DISPATCH(launch_balanced_one, a, mode, s);
+}
+
+int decode_balanced_occupancy(int d, int gt) { TA_DISPATCH(balanced_occupancy_one); }
 
 }  // namespace ta

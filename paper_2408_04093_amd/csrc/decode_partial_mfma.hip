@@ -37,7 +37,7 @@
 // (kappa below) applied to P and V alike.
 #include <type_traits>
 
-#include "balanced_index.hpp"
+#include "balanced_walk.hpp"
 #include "chunking.hpp"
 #include "mfma_tile.hpp"
 #include "ta_internal.hpp"
@@ -898,83 +898,14 @@ __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, false)) decode_p
     process_range<D, MODE, NRB, false, SHARED ? kAuxShared : kAuxStream>(a, rg, smem, st);
 }
 
-// Balanced launch for ragged batches (lengths known only on the device).  The keys of all
-// (batch, kv head, token slice) segments are laid end to end and cut into W equal shares, one per
-// workgroup (W = compute units), so every workgroup streams the same number of bytes whatever the
-// mix of lengths; a share that crosses a segment boundary is processed as several pieces.  Piece
-// ids (workgroup index + segment index) are unique and the pieces of one segment are consecutive,
-// which is all the combine kernel needs.  Associativity (Section 5.1) makes the cut points free.
-//
-// Shares are equal in COST, not in keys: every non-empty segment is charged kPieceCost extra
-// "virtual keys" at its start for the fixed cost of a piece (q load, pipeline ramp, epilogue: ~3 us,
-// the time a CU streams ~200 keys), so a workgroup that gets a run of tiny sequences gets fewer of
-// them.  Without the charge a share made of ~100 tiny segments took 2x the time of the others.
-constexpr int kMaxBalancedB = 2048;   // sequences whose prefix sums fit the LDS table
-constexpr int kMinShareBytes = 512 * 256;    // never cut finer than this many bytes of K (512 keys at d = 128)
-constexpr int kPieceCostBytes = 256 * 256;   // bytes of K charged per non-empty segment (256 keys at d = 128)
-
+// Balanced launch for ragged batches: every workgroup walks its equal-cost share of all keys, piece
+// by piece (balanced_walk.hpp).
 template <int D, int MODE, int NRB>
 __global__ void __launch_bounds__(kThreads, waves_per_simd(NRB, true)) decode_balanced_mfma_kernel(const PartialArgs a) {
     __shared__ __attribute__((aligned(16))) char smem[smem_bytes<D, NRB>()];
     __shared__ WaveStats<NRB> st;
-    __shared__ int64_t sh_cum[kMaxBalancedB + 1];
-    __shared__ int64_t sh_scan[kWaves];
-    constexpr int kMinShare = kMinShareBytes / (2 * D), kPieceCost = kPieceCostBytes / (2 * D);   // in keys
-
-    const int tid = threadIdx.x;
-    auto len_of = [&](int bb) -> int64_t {   // virtual length of one segment of sequence bb
-        int64_t L = a.N;
-        if (a.valid_len) {
-            L = a.valid_len[bb];
-            L = L < 0 ? 0 : (L > a.N ? a.N : L);
-        }
-        return balanced::virtual_len(L, kPieceCost);
-    };
-    // exclusive prefix sums of the virtual lengths: each thread takes a run of sequences, then a
-    // 256-wide scan of the run totals
-    const int per = (a.B + kThreads - 1) / kThreads;
-    int64_t mine = 0;
-    for (int i = 0; i < per; ++i) {
-        const int bb = tid * per + i;
-        if (bb < a.B) mine += len_of(bb);
-    }
-    // inclusive scan: inside each wave by shuffles, then the 4 wave totals through LDS
-    int64_t incl = mine;
-    {
-        const int lane = tid & (kWave - 1);
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int64_t v = __shfl_up(incl, off);
-            if (lane >= off) incl += v;
-        }
-        if (lane == kWave - 1) sh_scan[tid >> 6] = incl;
-        __syncthreads();
-        int64_t base = 0;
-        for (int ww = 0; ww < (tid >> 6); ++ww) base += sh_scan[ww];
-        incl += base;
-    }
-    int64_t run = incl - mine;
-    for (int i = 0; i < per; ++i) {
-        const int bb = tid * per + i;
-        if (bb < a.B) {
-            sh_cum[bb] = run;
-            run += len_of(bb);
-        }
-    }
-    if (tid == kThreads - 1) sh_cum[a.B] = incl;
-    __syncthreads();
-    if (blockIdx.x == 0)   // the combine kernel reads the same table
-        for (int i = tid; i <= a.B; i += kThreads) a.cum[i] = sh_cum[i];
-
-    // this workgroup's share of all (virtual) keys, piece by piece (balanced_index.hpp)
-    const int64_t G = (int64_t)a.Hkv * a.slices;
-    bool first = true;
-    balanced::for_each_piece(sh_cum, a.B, G, a.W, kMinShare, kPieceCost, (int)blockIdx.x, [&](const balanced::Piece &pc) {
-        const Range rg{pc.b, (int)(pc.j / a.slices), (int)(pc.j % a.slices), pc.k0, pc.n, pc.L, pc.id};
-        if (!first) __syncthreads();           // the previous piece's epilogue still reads LDS
-        first = false;
-        process_range<D, MODE, NRB, true>(a, rg, smem, st);
-    });
+    __shared__ BalancedShared walk;
+    balanced_walk<kThreads, 2 * D>(a, walk, [&](const Range &rg) { process_range<D, MODE, NRB, true>(a, rg, smem, st); });
 }
 
 }  // namespace
@@ -1023,8 +954,5 @@ hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hi
     return hipErrorInvalidValue;
 }
 
-int balanced_max_batch() { return kMaxBalancedB; }
-int balanced_min_share(int d) { return kMinShareBytes / (2 * d); }
-int balanced_piece_cost(int d) { return kPieceCostBytes / (2 * d); }
 
 }  // namespace ta

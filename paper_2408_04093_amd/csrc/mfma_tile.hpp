@@ -64,13 +64,4 @@ enum { kFull = 0, kEnergy = 1, kGradient = 2 };
 // probability ~R/t, i.e. on most steps of a 4096-key chunk once 16 or more rows are live.
 constexpr float kLazy = 8.0f;
 
-// Where one range of keys of one (batch, kv head, token slice) goes.
-struct Range {
-    int b, hk, slice;
-    int64_t lo;     // first key
-    int n;          // number of keys
-    int64_t L;      // valid length of the sequence (causal limits among query tokens)
-    int64_t slot;   // chunked launch: chunk index; balanced launch: piece id
-};
-
 }  // namespace ta

@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <mutex>
 
+#include "balanced_walk.hpp"
 #include "ta_internal.hpp"
 
 namespace {
@@ -18,6 +19,7 @@ inline int tokens(const ta_problem *p) { return p->Sq > 1 ? p->Sq : 1; }
 constexpr int kMaxRows = 64;
 inline int64_t total_rows(const ta_problem *p) { return (int64_t)tokens(p) * (p->Hq / p->Hkv); }
 inline int rows_per_slice(const ta_problem *p) {
+    if (!use_mfma_path(p->qkv_dtype, p->d)) return heads_per_workgroup(p->qkv_dtype, p->d, (int)total_rows(p));
     return (int)(total_rows(p) < kMaxRows ? total_rows(p) : kMaxRows);
 }
 // independent workgroup groups per chunk index
@@ -166,11 +168,11 @@ int32_t suggest_chunks(const ta_problem *p, int cus) {
 // chunks, but 1024 groups of N = 1024 keys 66 us against 61 us; hence no balanced launch for
 // more groups than CUs when a sequence cannot exceed 4096 keys (at d = 128).
 inline bool use_balanced(const ta_problem *p) {
-    if (p->valid_len == nullptr || !use_mfma_path(p->qkv_dtype, p->d) || p->B > balanced_max_batch()) return false;
+    if (p->valid_len == nullptr || p->B > kMaxBalancedB) return false;
     if (p->N > max_chunk_keys(p)) return false;   // a piece may be a whole sequence
     const int64_t groups = launch_groups(p), cus = device_compute_units();
     if (groups <= cus) return true;
-    return groups <= 4 * cus && p->N * p->d >= (int64_t)4096 * 128;
+    return groups <= 4 * cus && p->N * p->d * elem_bytes(p->qkv_dtype) >= (int64_t)4096 * 128 * 2;
 }
 
 struct BalancedPlan {
@@ -183,7 +185,8 @@ struct BalancedPlan {
 BalancedPlan balanced_plan(const ta_problem *p, int cus) {
     BalancedPlan b{};
     const int64_t groups = launch_groups(p);
-    b.W = cus;
+    // one workgroup per compute unit (matrix-core kernel), or as many as are resident (vector-ALU kernel)
+    b.W = use_mfma_path(p->qkv_dtype, p->d) ? cus : cus * decode_balanced_occupancy(p->d, rows_per_slice(p));
     b.pieces = b.W + groups;
     b.rows = rows_per_slice(p);
     const size_t slots = (size_t)b.pieces * b.rows;
@@ -278,14 +281,19 @@ ta_status run_balanced(const ta_problem *p, const void *q, const void *K, const 
     a.lse_in = mode == 2 ? lse : nullptr;
     a.W = bp.W;
     a.piece_rows = bp.rows;
-    if (launch_decode_balanced_mfma(a, p->d, mode, static_cast<hipStream_t>(stream)) != hipSuccess) return TA_ERR_HIP;
+    const hipError_t el = use_mfma_path(p->qkv_dtype, p->d)
+                              ? launch_decode_balanced_mfma(a, p->d, mode, static_cast<hipStream_t>(stream))
+                              : launch_decode_balanced(a, p->d, mode, static_cast<hipStream_t>(stream));
+    if (el != hipSuccess) return TA_ERR_HIP;
     CombineArgs c{};
     c.part_m = a.part_m; c.part_l = a.part_l; c.part_o = a.part_o;
     c.out = out; c.lse = lse;
     c.B = p->B; c.Hq = tokens(p) * p->Hq; c.P = 0;
     c.out_dtype = p->out_dtype;
     c.cum = a.cum;
-    c.W = bp.W; c.min_share = balanced_min_share(p->d); c.piece_cost = balanced_piece_cost(p->d); c.piece_rows = bp.rows;
+    const int row_bytes = p->d * elem_bytes(p->qkv_dtype);
+    c.W = bp.W; c.min_share = balanced_min_share_keys(row_bytes); c.piece_cost = balanced_piece_cost_keys(row_bytes);
+    c.piece_rows = bp.rows;
     c.heads = p->Hq; c.g = a.g; c.Hkv = p->Hkv; c.slices = a.slices; c.rows = a.rows;
     const hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = mode == 1 ? launch_energy_combine(c, s)

@@ -87,9 +87,9 @@ int decode_partial_occupancy(int dtype, int d, int gt);
 hipError_t launch_decode_partial_mfma(const PartialArgs &a, int d, int mode, hipStream_t s);
 // mode: 0 = (m,l,o), 1 = energy pass, 2 = gradient pass
 hipError_t launch_decode_balanced_mfma(const PartialArgs &a, int d, int mode, hipStream_t s);
-int balanced_max_batch();
-int balanced_min_share(int d);     // virtual keys
-int balanced_piece_cost(int d);    // virtual keys
+// balanced launch of the vector-ALU kernel (fp32 K/V), same modes; resident workgroups per compute unit
+hipError_t launch_decode_balanced(const PartialArgs &a, int d, int mode, hipStream_t s);
+int decode_balanced_occupancy(int d, int gt);
 hipError_t launch_tree_combine(const CombineArgs &a, int d, hipStream_t s);
 
 }  // namespace ta

@@ -971,3 +971,39 @@ def test_multi_token_four_row_blocks_every_length_of_the_steady_loop(N, d):
     w2 = W.make_multi(2, 8, 16, 2, d, N, torch.bfloat16, seed=5200 + N + d, device="cuda")
     w2.valid_len = torch.tensor([N, N - 37], dtype=torch.int32, device="cuda")
     check_multi(w2)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_skewed_ragged_batch_fp32_kv(d):
+    """fp32 K/V on the balanced launch of the vector-ALU kernel: one long sequence among many short
+    and empty ones, so pieces cross sequence, head and row-slice boundaries; the full pass, the
+    energy pass and the two-pass route, one and several query tokens, padding poisoned."""
+    B, N = 20, 20000
+    w = W.make_qkv(B, 8, 2, d, N, torch.float32, seed=181, device="cuda")
+    g = torch.Generator().manual_seed(18)
+    vl = torch.randint(1, 300, (B,), generator=g, dtype=torch.int32)
+    vl[3] = N; vl[0] = 0; vl[7] = 0; vl[19] = 0; vl[11] = 1; vl[12] = 2
+    w.valid_len = vl.cuda()
+    for b in range(B):
+        w.K[b, :, int(vl[b]):] = float("nan")
+        w.V[b, :, int(vl[b]):] = float("nan")
+    ref_out, ref_lse = oracle.decode(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl.numpy())
+    out, lse = ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    out2, lse2 = ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    for o, l in ((out, lse), (out2, lse2)):
+        assert row_rel_l2(o.cpu().numpy(), ref_out) <= TOL_F32
+        assert lse_err(l.cpu().numpy(), ref_lse) <= TOL_LSE
+        assert not o[0].any().item() and torch.isneginf(l[[0, 7, 19]]).all()
+    assert lse_err(lse_e.cpu().numpy(), ref_lse) <= TOL_LSE
+    # several query tokens: 3 x 6 = 18 rows per kv head = 9 slices of 2 rows, each an own segment
+    wm = W.make_multi(5, 3, 12, 2, d, 6000, torch.float32, seed=182, device="cuda")
+    wm.valid_len = torch.tensor([6000, 2, 0, 700, 4321], dtype=torch.int32, device="cuda")
+    ref_out, ref_lse = oracle.decode_causal(wm.q.cpu(), wm.K.cpu(), wm.V.cpu(), wm.scale, wm.valid_len.cpu().numpy())
+    out, lse = ta.decode(wm.q, wm.K, wm.V, wm.scale, wm.valid_len, ta.TA_F32)
+    out2, lse2 = ta.decode_two_pass(wm.q, wm.K, wm.V, wm.scale, wm.valid_len, ta.TA_F32)
+    torch.cuda.synchronize()
+    for o, l in ((out, lse), (out2, lse2)):
+        assert row_rel_l2(o.cpu().numpy(), ref_out) <= TOL_F32
+        assert lse_err(l.cpu().numpy(), ref_lse) <= TOL_LSE
