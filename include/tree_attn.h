@@ -24,7 +24,7 @@
  *     division).  The paper treats heads as independent (Appendix C.1); the
  *     grouping only changes which K/V a head reads.  With bf16 inputs up to 64
  *     heads of a group are processed by the same workgroup so that K/V bytes
- *     are fetched once per group (fp32 inputs: up to 8 heads per pass).
+ *     are fetched once per group (fp32 inputs: up to 4 heads per pass).
  *   - Keys at positions >= valid_len[b] do not exist and are never read.
  *   - lse is the natural-log logsumexp of the scaled scores over the valid
  *     keys, i.e. the energy F(0) of Observation 1; out is dF/dzeta at 0.
@@ -49,7 +49,7 @@
  *     share one pass over K/V as long as Sq * (Hq/Hkv) <= 64; beyond that the
  *     (token, head) pairs of the group, taken token-major, are processed in
  *     slices of 64, each slice reading K/V once (bf16 inputs; fp32 inputs take
- *     the pairs in slices of up to 8).
+ *     the pairs in slices of up to 4).
  */
 #ifndef TREE_ATTN_H
 #define TREE_ATTN_H

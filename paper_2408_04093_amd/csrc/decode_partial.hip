@@ -8,8 +8,8 @@
 // by the max shift of Appendix F.
 //
 // Data movement (the whole cost: the kernel is HBM-bound)
-//   * A K or V row is D fp32 = 256 or 512 bytes.  A lane owns EPL = 8 (up to 4
-//     heads per workgroup) or 4 columns of the head dimension: LPR = D/EPL lanes
+//   * A K or V row is D fp32 = 256 or 512 bytes.  A lane owns EPL = 8 columns
+//     of the head dimension: LPR = D/EPL lanes
 //     share a row and fetch it with EPL/4 128-bit buffer loads, load j covering
 //     bytes [16 LPR j, 16 LPR (j+1)) of the row, so every load instruction reads
 //     RPW = 64/LPR contiguous pieces of 128-512 bytes.  Wider lanes mean fewer
@@ -22,12 +22,15 @@
 //   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
 //     while it computes the current one (register double buffering), so with
 //     8-16 resident waves a CU has tens of KB outstanding.
-//   * GT (query token, head-in-group) rows that share the KV head are scored
-//     against the same registers.  Rows are numbered token-major (token * g +
-//     head in group) and cut into slices of GT: with one query token and g <= 8
-//     every K/V byte is fetched once per group; several tokens (the causal
-//     energy of Appendix C.1 on the last Sq positions) take Sq g / GT passes,
-//     each row with its own causal limit.
+//   * GT <= 4 (query token, head-in-group) rows that share the KV head are
+//     scored against the same registers.  Rows are numbered token-major (token *
+//     g + head in group) and cut into slices of GT: with one query token and
+//     g <= 4 every K/V byte is fetched once per group; wider groups and several
+//     tokens (the causal energy of Appendix C.1 on the last Sq positions) take
+//     Sq g / GT passes, each row with its own causal limit, launched so that the
+//     slices of a chunk share it through L2.  (Eight rows per workgroup need 256
+//     registers for q and the numerators alone and run at one wave per SIMD:
+//     193 us for 8 rows against 2 x 72 us for two slices of 4.)
 //
 // Pass modes (the paper's Algorithm 3 against its Algorithms 1 and 2), as on the matrix-core kernel:
 //   kFull (m, l, o) per chunk; kEnergy (m, l) only, K is the only stream; kGradient
@@ -48,18 +51,17 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kLoadsPerStep = 4;  // 128-bit loads per lane, stream and pipeline step (keys x loads per key)
-constexpr int kAux = 2;           // cache-policy bits of the K/V buffer loads: 2 = non-temporal.  K/V are
-                                  // read once; streaming them non-temporally measured 7.0 TB/s against
-                                  // 6.2 TB/s for default-policy loads on a read-only probe.
+// cache-policy bits of the K/V buffer loads.  2 = non-temporal: K/V are read once, and streaming them
+// non-temporally measured 7.0 TB/s against 6.2 TB/s for default-policy loads on a read-only probe.
+// 0 = default, when several row slices stream the same chunk at the same time (several query tokens,
+// wide groups): what one workgroup fetched stays in its XCD's L2 for the others.
+constexpr int kAuxStream = 2, kAuxShared = 0;
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 
 constexpr int kBytes = 4;   // fp32 K/V
 using acc_t = double;       // score / running-max type
-// columns per lane: two 128-bit loads per row, one when 8 heads share the workgroup (q alone would
-// take 128 registers otherwise)
-constexpr int columns_per_lane(int gt) { return gt <= 4 ? 8 : 4; }
+constexpr int kColumnsPerLane = 8;   // two 128-bit loads per row and lane
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
     // raw buffer (stride 0): hardware returns 0 for any access past `bytes`
@@ -168,10 +170,11 @@ struct MergeShared {
 
 // The whole streaming computation for one range of keys of one (batch, kv head, row slice): called
 // once per workgroup by the chunked kernel and once per piece by the balanced kernel.
-template <int D, int GT, int MODE, bool BALANCED>
+template <int D, int GT, int MODE, bool BALANCED, int AUX>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &cr, MergeShared<D, GT> &lds) {
-    constexpr int EPL = columns_per_lane(GT), NL = EPL / 4;   // columns and 128-bit loads per lane and row
-    constexpr int U = NL == 2 ? 1 : kLoadsPerStep / NL;                     // keys per row group per pipeline step
+    constexpr int EPL = kColumnsPerLane, NL = EPL / 4;   // columns and 128-bit loads per lane and row
+    constexpr int U = 1;                                  // keys per row group per pipeline step (two: 288
+                                                          // registers at GT = 4, one wave per SIMD, slower)
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
     constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
 
@@ -257,13 +260,13 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int j = 0; j < NL; ++j)
-                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc + j * LPR * 16), 0, kAux);
+                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(koff[u] + kinc + j * LPR * 16), 0, AUX);
             if constexpr (MODE != kEnergy) {
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int j = 0; j < NL; ++j)
-                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc + j * LPR * 16), 0, kAux);
+                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(voff[u] + vinc + j * LPR * 16), 0, AUX);
             }
         } else {
             // ragged last step: rows past the chunk are redirected to its last
@@ -278,13 +281,13 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int j = 0; j < NL; ++j)
-                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + (j * LPR + sub) * 16), 0, kAux);
+                    T.k[u][j] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)(rc[u] * a.k_row_bytes + (j * LPR + sub) * 16), 0, AUX);
             if constexpr (MODE != kEnergy) {
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int j = 0; j < NL; ++j)
-                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + (j * LPR + sub) * 16), 0, kAux);
+                        T.v[u][j] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)(rc[u] * a.v_row_bytes + (j * LPR + sub) * 16), 0, AUX);
             }
         }
     };
@@ -387,14 +390,14 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
 }
 
 // Chunked launch: one workgroup per (batch, kv head, row slice, chunk).
-template <int D, int GT, int MODE>
+template <int D, int GT, int MODE, bool SHARED = false>
 __global__ void __launch_bounds__(kThreads) decode_partial_kernel(const PartialArgs a) {
     __shared__ MergeShared<D, GT> lds;
     __shared__ int sh_rank[kMaxRankedChunks + 1];
     const ChunkRange cr = select_chunk<kThreads>(a, sh_rank);
     if (cr.surplus) return;
     const Range rg{cr.b, cr.hk, cr.slice, cr.lo, cr.n, cr.L, cr.chunk};
-    process_range<D, GT, MODE, false>(a, rg, lds);
+    process_range<D, GT, MODE, false, SHARED ? kAuxShared : kAuxStream>(a, rg, lds);
 }
 
 // Balanced launch for ragged batches: every workgroup walks its equal-cost share of all keys, piece
@@ -403,12 +406,19 @@ template <int D, int GT, int MODE>
 __global__ void __launch_bounds__(kThreads) decode_balanced_kernel(const PartialArgs a) {
     __shared__ MergeShared<D, GT> lds;
     __shared__ BalancedShared walk;
-    balanced_walk<kThreads, kBytes * D>(a, walk, [&](const Range &rg) { process_range<D, GT, MODE, true>(a, rg, lds); });
+    balanced_walk<kThreads, kBytes * D>(a, walk, [&](const Range &rg) { process_range<D, GT, MODE, true, kAuxStream>(a, rg, lds); });
 }
 
 template <int D, int GT>
 hipError_t launch_one(const PartialArgs &a, int mode, hipStream_t s) {
     const dim3 grid((uint32_t)launch_blocks(a));
+    if (a.slices > 1) {   // several slices per (batch, kv head) stream the same K/V: share it through L2
+        switch (mode) {
+            case kEnergy: return launch_kernel(decode_partial_kernel<D, GT, kEnergy, true>, grid, dim3(kThreads), s, a);
+            case kGradient: return launch_kernel(decode_partial_kernel<D, GT, kGradient, true>, grid, dim3(kThreads), s, a);
+            default: return launch_kernel(decode_partial_kernel<D, GT, kFull, true>, grid, dim3(kThreads), s, a);
+        }
+    }
     switch (mode) {
         case kEnergy: return launch_kernel(decode_partial_kernel<D, GT, kEnergy>, grid, dim3(kThreads), s, a);
         case kGradient: return launch_kernel(decode_partial_kernel<D, GT, kGradient>, grid, dim3(kThreads), s, a);
@@ -424,7 +434,7 @@ int occupancy_one() {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, decode_partial_kernel<D, GT, kFull>, kThreads, 0) !=
                 hipSuccess || n < 1) {
             (void)hipGetLastError();
-            n = GT >= 8 ? 1 : GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
+            n = GT >= 4 ? 2 : GT >= 2 ? 3 : 4;   // what the gfx950 build gives
         }
         return n;
     }();
@@ -457,12 +467,10 @@ int balanced_occupancy_one() {
 
 #define TA_DISPATCH(FN, ...)                                                                   \
     do {                                                                                       \
-        if (d == 128) { switch (gt) { case 8: return FN<128, 8>(__VA_ARGS__);                  \
-                                      case 4: return FN<128, 4>(__VA_ARGS__);                  \
+        if (d == 128) { switch (gt) { case 4: return FN<128, 4>(__VA_ARGS__);                  \
                                       case 2: return FN<128, 2>(__VA_ARGS__);                  \
                                       default: return FN<128, 1>(__VA_ARGS__); } }             \
-        switch (gt) { case 8: return FN<64, 8>(__VA_ARGS__);                                   \
-                      case 4: return FN<64, 4>(__VA_ARGS__);                                   \
+        switch (gt) { case 4: return FN<64, 4>(__VA_ARGS__);                                   \
                       case 2: return FN<64, 2>(__VA_ARGS__);                                   \
                       default: return FN<64, 1>(__VA_ARGS__); }                                \
     } while (0)

@@ -69,10 +69,10 @@ hipError_t launch_sum_partials(const CombineArgs &a, int d, hipStream_t s);
 // fp32 on the VALU kernel.
 inline bool use_mfma_path(int dtype, int d) { return dtype == TA_BF16 && (d == 128 || d == 64); }
 
-// Heads of one GQA group handled by one workgroup for a given group size.
+// (token, head) rows of one kv head handled by one workgroup, given their number.
 inline int heads_per_workgroup(int dtype, int d, int g) {
     if (use_mfma_path(dtype, d)) return g;
-    for (int gt : {8, 4, 2}) if (g % gt == 0) return gt;
+    for (int gt : {4, 2}) if (g % gt == 0) return gt;   // vector-ALU kernel: 4, 2 or 1
     return 1;
 }
 

@@ -643,7 +643,7 @@ def test_maximum_query_tokens_and_a_very_long_chunk_table():
     (1, 2, 4, 1, 100, 64), (2, 4, 8, 2, 1000, 128), (1, 3, 8, 1, 513, 64), (1, 16, 1, 1, 777, 128),
     (1, 5, 6, 2, 2050, 128), (2, 7, 12, 2, 300, 64), (1, 6, 4, 1, 3, 128), (1, 4, 16, 2, 4099, 64)])
 def test_multi_token_fp32_kv(B, Sq, Hq, Hkv, N, d):
-    """Several query tokens with fp32 K/V (vector-ALU kernel: (token, head) rows in slices of up to 8,
+    """Several query tokens with fp32 K/V (vector-ALU kernel: (token, head) rows in slices of up to 4,
     each row with its own causal limit), the full pass, the energy pass and the two-pass route, also
     ragged and with more tokens than keys."""
     w = W.make_multi(B, Sq, Hq, Hkv, d, N, torch.float32, seed=900 + Sq + N, device="cuda")
