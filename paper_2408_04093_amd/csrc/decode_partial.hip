@@ -85,77 +85,78 @@ struct Tile {
     v4i v[U][EPL / 4];
 };
 
+// The scores of a key against the GT rows are summed across the lanes of a row as a reduce-scatter
+// (scatter_sum in wave_ops.hpp): a lane ends with the score of ONE row, its "own" row, and keeps the
+// running max and the normaliser of that row only; the exponential of a score is evaluated once per
+// owner instead of by every lane, and the GT weights travel back to all lanes for the numerators.
+// Per-row registers of a lane (q, o, weights) are indexed by slot: slot j holds row (j ^ own row).
 template <int GT, int EPL>
 struct State {
-    acc_t m[GT];        // running max, log2 units
-    float l[GT];        // running normaliser
-    float o[GT][EPL];   // running numerator, this lane's columns
+    acc_t m;            // running max of the lane's own row, log2 units
+    float l;            // running normaliser of the lane's own row
+    float o[GT][EPL];   // running numerators, [slot][this lane's columns]
 };
 
 __device__ __forceinline__ acc_t neg_inf() { return -__builtin_huge_val(); }
 
-// One pipeline step: U keys per row group, GT heads.
+// One pipeline step: U keys per row group, GT rows.
 //   row0: chunk-relative index of this lane's first key (u = 0); key u is
-//   row0 + u*RPW.  MASKED steps treat keys >= lim[h] as absent for row h (the end of the chunk, or
-//   the row's causal limit inside it).
+//   row0 + u*RPW.  MASKED steps treat keys >= lim_own as absent for the lane's own row (the end of
+//   the chunk, or the row's causal limit inside it).
 template <int D, int GT, int U, int EPL, bool MASKED, int MODE>
 __device__ __forceinline__ void step(const Tile<U, EPL> &T, const double (&q)[GT][EPL], State<GT, EPL> &st, acc_t c,
-                                     int row0, const int (&lim)[GT]) {
+                                     int row0, int lim_own) {
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
 
-    acc_t s2[U][GT];
+    acc_t s2[U];   // score of key u against the lane's own row
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        acc_t x[GT];
 #pragma unroll
-        for (int h = 0; h < GT; ++h) {
-            acc_t acc = group_sum<LPR>(lane_dot<EPL>(T.k[u], q[h]));
-            s2[u][h] = acc * c;
-            if constexpr (MASKED)
-                if (row0 + u * RPW >= lim[h]) s2[u][h] = neg_inf();
-        }
+        for (int j = 0; j < GT; ++j) x[j] = lane_dot<EPL>(T.k[u], q[j]);
+        s2[u] = scatter_sum<LPR, GT>(x) * c;
+        if constexpr (MASKED)
+            if (row0 + u * RPW >= lim_own) s2[u] = neg_inf();
     }
 
     // Raise the running max only when some lane of the wave needs it; once the
     // stream is warm this is rare and the rescale of o is skipped.  (Gradient pass: the shift is the
     // given logsumexp and never moves.)
-    acc_t mt[GT];
-    bool need = false;
     if constexpr (MODE != kGradient) {
+        acc_t mt = s2[0];
 #pragma unroll
-        for (int h = 0; h < GT; ++h) {
-            mt[h] = s2[0][h];
+        for (int u = 1; u < U; ++u) mt = fmax(mt, s2[u]);
+        const bool up = mt > st.m;
+        if (__builtin_amdgcn_ballot_w64(up) != 0) {
+            const float alpha = up ? exp2_hw((float)(st.m - mt)) : 1.0f;
+            st.m = up ? mt : st.m;
+            st.l *= alpha;
+            if constexpr (MODE != kEnergy) {
+                float al[GT];
+                scatter_gather<LPR, GT>(alpha, al);
 #pragma unroll
-            for (int u = 1; u < U; ++u) mt[h] = fmax(mt[h], s2[u][h]);
-            need |= mt[h] > st.m[h];
-        }
-    }
-    if (MODE != kGradient && __builtin_amdgcn_ballot_w64(need) != 0) {
+                for (int j = 0; j < GT; ++j)
 #pragma unroll
-        for (int h = 0; h < GT; ++h) {
-            const bool up = mt[h] > st.m[h];
-            const float alpha = up ? exp2_hw((float)(st.m[h] - mt[h])) : 1.0f;
-            st.m[h] = up ? mt[h] : st.m[h];
-            st.l[h] *= alpha;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) st.o[h][e] *= alpha;
+                    for (int e = 0; e < EPL; ++e) st.o[j][e] *= al[j];
+            }
         }
     }
 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        float vf[EPL];
+        float p = exp2_hw((float)(s2[u] - st.m));
+        if constexpr (MASKED)
+            if (row0 + u * RPW >= lim_own) p = 0.f;
+        st.l += p;
+        if constexpr (MODE != kEnergy) {
+            float vf[EPL], ph[GT];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) vf[e] = MODE != kEnergy ? __int_as_float(T.v[u][e >> 2][e & 3]) : 0.f;
+            for (int e = 0; e < EPL; ++e) vf[e] = __int_as_float(T.v[u][e >> 2][e & 3]);
+            scatter_gather<LPR, GT>(p, ph);
 #pragma unroll
-        for (int h = 0; h < GT; ++h) {
-            float p = exp2_hw((float)(s2[u][h] - st.m[h]));
-            if constexpr (MASKED)
-                if (row0 + u * RPW >= lim[h]) p = 0.f;
-            st.l[h] += p;
-            if constexpr (MODE != kEnergy) {
+            for (int j = 0; j < GT; ++j)
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) st.o[h][e] = fmaf(p, vf[e], st.o[h][e]);
-            }
+                for (int e = 0; e < EPL; ++e) st.o[j][e] = fmaf(ph[j], vf[e], st.o[j][e]);
         }
     }
 }
@@ -220,14 +221,20 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         lim[h] = (int)(l < 0 ? 0 : (l > n ? n : l));
     }
 
-    // q: this lane's EPL columns of each head, kept in registers.  Element e = 4 j + r of a lane is
-    // column 4 (j LPR + sub) + r: load j of a row, this lane's 16 bytes of it.
+    // the row this lane ends up holding the scores of, and its limit
+    const int own = scatter_own<LPR, GT>(sub);
+    int lim_own = lim[0];
+#pragma unroll
+    for (int h = 1; h < GT; ++h) lim_own = own == h ? lim[h] : lim_own;
+
+    // q: this lane's EPL columns of each row, kept in registers, slot j = row j ^ own.  Element
+    // e = 4 j + r of a lane is column 4 (j LPR + sub) + r: load j of a row, this lane's 16 bytes of it.
     double q[GT][EPL];
 #pragma unroll
     for (int h = 0; h < GT; ++h) {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const char *qp = (const char *)a.q + (vrow(h) * D + 4 * (j * LPR + sub)) * kBytes;
+            const char *qp = (const char *)a.q + (vrow(h ^ own) * D + 4 * (j * LPR + sub)) * kBytes;
             const v4i raw = *reinterpret_cast<const v4i *>(qp);
 #pragma unroll
             for (int r = 0; r < 4; ++r) q[h][4 * j + r] = (double)__int_as_float(raw[r]);
@@ -293,25 +300,24 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     };
 
     State<GT, EPL> st;
+    st.m = neg_inf();
+    st.l = 0.f;
+    if constexpr (MODE == kGradient) {
+        // the shift is the given total logsumexp (natural log -> log2 units); a row with no key at
+        // all (lse = -inf) gets +inf so that every exponential below is exactly 0
+        const float given = a.lse_in[vrow(own)];
+        st.m = given == -__builtin_huge_valf() ? __builtin_huge_val() : (acc_t)given * (acc_t)kLog2e;
+    }
 #pragma unroll
-    for (int h = 0; h < GT; ++h) {
-        st.m[h] = neg_inf();
-        st.l[h] = 0.f;
-        if constexpr (MODE == kGradient) {
-            // the shift is the given total logsumexp (natural log -> log2 units); a row with no key at
-            // all (lse = -inf) gets +inf so that every exponential below is exactly 0
-            const float given = a.lse_in[vrow(h)];
-            st.m[h] = given == -__builtin_huge_valf() ? __builtin_huge_val() : (acc_t)given * (acc_t)kLog2e;
-        }
+    for (int h = 0; h < GT; ++h)
 #pragma unroll
         for (int e = 0; e < EPL; ++e) st.o[h][e] = 0.f;
-    }
     const acc_t c = (acc_t)a.c;
 
     auto compute = [&](const Tile<U, EPL> &T, int it) {
         const int row0 = it * ROWS_ITER + row_lane;
-        if (it < n_full) step<D, GT, U, EPL, false, MODE>(T, q, st, c, row0, lim);
-        else step<D, GT, U, EPL, true, MODE>(T, q, st, c, row0, lim);
+        if (it < n_full) step<D, GT, U, EPL, false, MODE>(T, q, st, c, row0, lim_own);
+        else step<D, GT, U, EPL, true, MODE>(T, q, st, c, row0, lim_own);
     };
 
     // two register tiles, ping-pong: the loads of step it+1 are in flight
@@ -326,15 +332,20 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         compute(tb, it + 1);
     }
 
-    // ---- merge the RPW row groups of this wave (lanes LPR apart)
+    // ---- merge the RPW row groups of this wave (lanes LPR apart: they own the same row)
+    {
+        const acc_t mw = across_groups_max<LPR>(st.m);
+        const float f = (st.m == mw) ? 1.0f : exp2_hw((float)(st.m - mw));
+        st.m = mw;
+        st.l = across_groups_sum<LPR>(st.l * f);
+        if constexpr (MODE != kEnergy) {
+            float fs[GT];
+            scatter_gather<LPR, GT>(f, fs);
 #pragma unroll
-    for (int h = 0; h < GT; ++h) {
-        const acc_t mw = across_groups_max<LPR>(st.m[h]);
-        const float f = (st.m[h] == mw) ? 1.0f : exp2_hw((float)(st.m[h] - mw));
-        st.m[h] = mw;
-        st.l[h] = across_groups_sum<LPR>(st.l[h] * f);
+            for (int h = 0; h < GT; ++h)
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) st.o[h][e] = across_groups_sum<LPR>(st.o[h][e] * f);
+                for (int e = 0; e < EPL; ++e) st.o[h][e] = across_groups_sum<LPR>(st.o[h][e] * fs[h]);
+        }
     }
 
     // ---- merge the waves of the workgroup through LDS
@@ -342,16 +353,15 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     auto &lds_l = lds.l;
     auto &lds_m = lds.m;
     if (rg == 0) {
+        if constexpr (MODE != kEnergy) {
 #pragma unroll
-        for (int h = 0; h < GT; ++h)
+            for (int h = 0; h < GT; ++h)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) lds_o[w][h][4 * ((e >> 2) * LPR + sub) + (e & 3)] = st.o[h][e];
-    }
-    if (lane == 0) {
-#pragma unroll
-        for (int h = 0; h < GT; ++h) {
-            lds_m[w][h] = st.m[h];
-            lds_l[w][h] = st.l[h];
+                for (int e = 0; e < EPL; ++e) lds_o[w][h ^ own][4 * ((e >> 2) * LPR + sub) + (e & 3)] = st.o[h][e];
+        }
+        if (sub == own * (LPR / GT)) {   // the first of the lanes that own this row
+            lds_m[w][own] = st.m;
+            lds_l[w][own] = st.l;
         }
     }
     __syncthreads();
@@ -367,7 +377,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             const acc_t mw = lds_m[ww][h];
             const float f = (mw == ms) ? 1.0f : exp2_hw((float)(mw - ms));
             lt = fmaf(f, lds_l[ww][h], lt);
-            ot = fmaf(f, lds_o[ww][h][col], ot);
+            if constexpr (MODE != kEnergy) ot = fmaf(f, lds_o[ww][h][col], ot);
         }
         // Natural-log units for the stored max.  The fp32 value written is not
         // exactly ms*ln2, so l and o are rescaled by the (tiny) residual to stay

@@ -45,6 +45,52 @@ __device__ __forceinline__ F group_sum(F x) {
     return x;
 }
 
+// N sums at once over groups of LANES consecutive lanes (LANES in {8,16}, N in {1,2,4}), as a
+// reduce-scatter: every lane ends with ONE of the N totals instead of all of them, at log2(LANES) + N - 1
+// additions instead of N log2(LANES).  A lane's inputs are numbered by "slot": slot j of a lane is
+// total (j ^ own), where own = scatter_own(lane in group) is the total the lane ends with (its slot 0).
+// The exchange steps pair lanes whose `own` differ (by 3, then by 1, for N = 4), so each lane adds what
+// its partner holds for the lane's own totals: no selects.  The remaining steps are plain sums among the
+// LANES / N lanes that own the same total, all of which end with it.
+template <int LANES, int N>
+__device__ __forceinline__ int scatter_own(int lane_in_group) { return lane_in_group / (LANES / N); }
+
+template <int LANES, int N, typename F>
+__device__ __forceinline__ F scatter_sum(const F (&x)[N]) {
+    static_assert((LANES == 8 || LANES == 16) && (N == 1 || N == 2 || N == 4), "unsupported shape");
+    constexpr int kA = LANES == 16 ? kDppMirror : kDppHalfMirror;   // flips every bit of the lane index in the group
+    if constexpr (N == 1) {
+        return group_sum<LANES>(x[0]);
+    } else if constexpr (N == 2) {       // own = top bit
+        F y = x[0] + dpp<kA>(x[1]);
+        y += dpp<kDppXor1>(y);
+        y += dpp<kDppXor2>(y);
+        if constexpr (LANES == 16) y += dpp<kDppHalfMirror>(y);
+        return y;
+    } else {                             // own = top two bits
+        constexpr int kB = LANES == 16 ? kDppHalfMirror : kDppXor2;   // flips the second bit, keeps the top one
+        const F y0 = x[0] + dpp<kA>(x[3]), y1 = x[1] + dpp<kA>(x[2]);
+        F z = y0 + dpp<kB>(y1);
+        z += dpp<kDppXor1>(z);
+        if constexpr (LANES == 16) z += dpp<kDppXor2>(z);
+        return z;
+    }
+}
+
+// The inverse: every lane contributes the value of its own total and receives all N, in slot order.
+template <int LANES, int N>
+__device__ __forceinline__ void scatter_gather(float own, float (&p)[N]) {
+    constexpr int kA = LANES == 16 ? kDppMirror : kDppHalfMirror;
+    p[0] = own;
+    if constexpr (N == 2) p[1] = dpp<kA>(own);
+    if constexpr (N == 4) {
+        constexpr int kB = LANES == 16 ? kDppHalfMirror : kDppXor2;
+        p[1] = dpp<kB>(own);
+        p[3] = dpp<kA>(own);
+        p[2] = dpp<kA>(p[1]);
+    }
+}
+
 // Reductions across the groups of a wave (lane distance >= LANES).
 template <int LANES, typename F>
 __device__ __forceinline__ F across_groups_max(F x) {
