@@ -13,10 +13,10 @@
 //     share a row and fetch it with EPL/4 128-bit buffer loads, load j covering
 //     bytes [16 LPR j, 16 LPR (j+1)) of the row, so every load instruction reads
 //     RPW = 64/LPR contiguous pieces of 128-512 bytes.  Wider lanes mean fewer
-//     lanes per row: the cross-lane sum of a score takes log2(LPR) steps and the
-//     exponential of a score is evaluated by LPR lanes, and both are what this
-//     kernel spends its time on (EPL = 4 -> 8 at d = 128: 9.5 -> 5 vector
-//     instructions per key and head for the score).
+//     lanes per row, and the cross-lane sums of the scores are what this kernel
+//     spends its time on besides the fp64 products (EPL = 4 -> 8 at d = 128:
+//     9.5 -> 5 vector instructions per key and head for the score; summed as a
+//     reduce-scatter over the GT rows, see State: 16 -> 5 fp64 additions per key at GT = 4).
 //   * Each lane belongs to one of RPW interleaved "row groups" of keys.
 //     Each row group runs its own online softmax; they are merged at the end.
 //   * Each wave keeps U K-loads and U V-loads of the NEXT step in flight
@@ -174,8 +174,10 @@ struct MergeShared {
 template <int D, int GT, int MODE, bool BALANCED, int AUX>
 __device__ __forceinline__ void process_range(const PartialArgs &a, const Range &cr, MergeShared<D, GT> &lds) {
     constexpr int EPL = kColumnsPerLane, NL = EPL / 4;   // columns and 128-bit loads per lane and row
-    constexpr int U = 1;                                  // keys per row group per pipeline step (two: 288
-                                                          // registers at GT = 4, one wave per SIMD, slower)
+    // keys per row group per pipeline step.  One with V in the stream (two: 288 registers at GT = 4, one
+    // wave per SIMD, slower); two in the energy pass, whose tiles are half the bytes and whose lanes hold no
+    // numerators (64k fp32 keys: 45.3 us against 48.5 with one and 49.6 with four)
+    constexpr int U = MODE == kEnergy ? 2 : 1;
     constexpr int LPR = D / EPL, RPW = kWave / LPR;
     constexpr int ROWS_WAVE = U * RPW, ROWS_ITER = kWaves * ROWS_WAVE;
 
