@@ -466,13 +466,14 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // Probabilities of one row block from its scores: p = 2^(s c - shift), the lane's share of the
     // normaliser, and (unless only the energy is wanted) P = hi + lo as MFMA A operand: lane
     // (r, row c), k = 8r + e.
-    auto make_p = [&](auto tail_c, int rb, bf16x8 &hi, bf16x8 &lo) {
-        constexpr bool masked = decltype(tail_c)::value;
+    // (SHIFTED: sv already holds s c - shift, as the pipelined loop leaves it.)
+    auto make_p = [&](auto tail_c, auto shifted_c, int rb, bf16x8 &hi, bf16x8 &lo) {
+        constexpr bool masked = decltype(tail_c)::value, shifted = decltype(shifted_c)::value;
         float p[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            p[e] = exp2_hw(fmaf(sv[rb][e], cs, -m_run[rb]));
-            if constexpr (masked)
+            p[e] = exp2_hw(shifted ? sv[rb][e] : fmaf(sv[rb][e], cs, -m_run[rb]));
+            if constexpr (masked && !shifted)
                 if (sv[rb][e] == -__builtin_huge_valf()) p[e] = 0.f;   // also when m_run is still -inf
             l_run[rb] += p[e];
         }
@@ -503,11 +504,11 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         return __builtin_bit_cast(bf16x8, v4i{(int)bj[0], (int)bj[1], (int)bj[2], (int)bj[3]});
     };
 
-    auto back = [&](auto tail_c, row_t (&vr)[8], int it) {
+    auto back = [&](auto tail_c, auto shifted_c, row_t (&vr)[8], int it) {
         constexpr bool masked = decltype(tail_c)::value;
         bf16x8 pa_hi[NRB], pa_lo[NRB];
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) make_p(tail_c, rb, pa_hi[rb], pa_lo[rb]);
+        for (int rb = 0; rb < NRB; ++rb) make_p(tail_c, shifted_c, rb, pa_hi[rb], pa_lo[rb]);
         if constexpr (MODE != kEnergy) {
             // ---- PV: each of this lane's columns goes into B layout once for all row blocks
 #pragma unroll
@@ -554,7 +555,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         // slice k = 0..15 of one row block's exponentials and P split: three vector instructions
         auto p_slice = [&](int rb, int k) {
             if (k < 8) {
-                pn[k] = exp2_hw(fmaf(sv[rb][k], cs, -m_run[rb]));
+                pn[k] = exp2_hw(sv[rb][k]);   // sv is s c - shift inside this loop
                 l_run[rb] += pn[k];
             } else {
                 const int x = (k - 8) >> 1;
@@ -630,7 +631,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
                     constexpr int kPer = kPV / NRB;            // slots per row block: 4 or 2
                     const int mb = i / kPer, part = i % kPer;
 #pragma unroll
-                    for (int e = part * 8 / kPer; e < (part + 1) * 8 / kPer; ++e) sv[mb][e] = sn[mb][e >> 2][e & 3];
+                    for (int e = part * 8 / kPer; e < (part + 1) * 8 / kPer; ++e)
+                        sv[mb][e] = fmaf(sn[mb][e >> 2][e & 3], cs, -m_run[mb]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -659,7 +661,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             finish_q();
             for (; it < n_steady; ++it) {
                 if (front(std::false_type{}, kr, ka, it)) raise();
-                back(std::false_type{}, vr, it);
+                back(std::false_type{}, std::false_type{}, vr, it);
             }
         } else {
             if constexpr (kDirectK) issue_kd(ka, 0); else issue_k(kr, 0);
@@ -668,7 +670,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
         for (; it < n_iters; ++it) {   // last full tile, ragged tail, causal limits
             if (front(std::true_type{}, kr, ka, it)) raise();
-            back(std::true_type{}, vr, it);
+            back(std::true_type{}, std::false_type{}, vr, it);
         }
     } else {
         // rotated: the scores and maxima of a step are made during the step before
@@ -680,10 +682,31 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             pending = front(std::false_type{}, kr, ka, 0);   // S(0); leaves the K tile of step 1 in flight
             __builtin_amdgcn_sched_barrier(0);
             issue_v_full(vr, 0);
+            // Inside the loop the score registers hold s c - shift instead of s: the step writes them
+            // with the multiply-add that the exponentials need anyway, in place of a move.  A shift that
+            // moves afterwards (rare) takes the difference out again.
+            if (pending) raise();
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sv[rb][e] = fmaf(sv[rb][e], cs, -m_run[rb]);
             for (; it < n_steady; ++it) {
-                if (pending) raise();
                 pending = pipelined_step(vr, ka, it);
+                if (pending) {
+                    float m_old[NRB];
+#pragma unroll
+                    for (int rb = 0; rb < NRB; ++rb) m_old[rb] = m_run[rb];
+                    raise();
+#pragma unroll
+                    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) sv[rb][e] -= m_run[rb] - m_old[rb];
+                }
             }
+            // the first step after the loop finds its scores in that form, shifts already raised
+            back(std::true_type{}, std::true_type{}, vr, it);
+            if (it + 1 < n_iters) pending = front(std::true_type{}, kr, ka, it + 1);
+            ++it;
         } else {
             issue_kd(ka, 0);
             issue_v(vr, 0);
@@ -692,7 +715,7 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
         }
         for (; it < n_iters; ++it) {   // last full tiles, ragged tail, causal limits
             if (pending) raise();
-            back(std::true_type{}, vr, it);
+            back(std::true_type{}, std::false_type{}, vr, it);
             if (it + 1 < n_iters) pending = front(std::true_type{}, kr, ka, it + 1);
         }
     }
