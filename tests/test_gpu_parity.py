@@ -410,6 +410,41 @@ def test_scores_rising_along_the_sequence_move_the_shift_at_every_step(Sq, d):
             check(w, f32_out_tol=2e-4)
 
 
+@pytest.mark.parametrize("Sq,Hq,Hkv,d", [(1, 8, 2, 128), (1, 8, 2, 64), (1, 4, 2, 128), (3, 8, 2, 64), (1, 3, 1, 128)])
+def test_scores_rising_along_the_sequence_fp32_kv(Sq, Hq, Hkv, d):
+    """The same ramp with fp32 K/V: on the vector-ALU kernel a lane keeps the running max of ONE of
+    the workgroup's rows, and when it moves, the factor that rescales the numerators of all rows has
+    to reach every lane (4, 2 and 1 rows per workgroup, both head dimensions, several tokens).  Scores
+    are fp64 there, so the fp32 bar of 1e-5 holds although they reach ~150."""
+    B, N = 2, 3000
+    g = torch.Generator().manual_seed(600 + Sq + d + Hq)
+    u = torch.randn(d, generator=g)
+    u /= u.norm()
+    shape_q = (B, Sq, Hq, d) if Sq > 1 else (B, Hq, d)
+    q = 2.0 * u + 0.3 * torch.randn(shape_q, generator=g)
+    ramp = torch.arange(N, dtype=torch.float32) / 16.0          # a wave sees a key of its row group every 16 keys
+    K = 3.25 * ramp[:, None] * u[None, :] / 8.0 + 0.5 * torch.randn((B, Hkv, N, d), generator=g)
+    V = torch.randn((B, Hkv, N, d), generator=g)
+    for Kx in (K, K.flip(2).contiguous()):
+        w = W.Workload("ramp32", q.cuda(), Kx.cuda(), V.cuda(), 1.0)
+        w.valid_len = torch.tensor([N, 1777], dtype=torch.int32, device="cuda")
+        vl = w.valid_len.cpu().numpy()
+        if Sq > 1:
+            ref_out, ref_lse = oracle.decode_causal(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
+        else:
+            ref_out, ref_lse = oracle_of(w)
+        assert np.abs(ref_lse).max() > 100
+        for valid_len in (w.valid_len, None):
+            if valid_len is None and Sq == 1:
+                ref_out, ref_lse = oracle.decode(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, None)
+            elif valid_len is None:
+                ref_out, ref_lse = oracle.decode_causal(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, None)
+            out, lse = ta.decode(w.q, w.K, w.V, w.scale, valid_len, ta.TA_F32)
+            torch.cuda.synchronize()
+            assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_F32
+            assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_seeded_random_problems_against_the_oracle(seed):
     """Shapes drawn from a seeded generator: batch, tokens, group size (1..80, so up to several row
