@@ -537,7 +537,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     //                   under the V tile's interleave and the first row block's exponentials / P split
     //     slots 32-79   PV of row block rb under the exponentials / P split of row block rb + 1 and the
     //                   lane maxima of S(it + 1)
-    //     slots 80-95   PV of the last row block under the move of S(it + 1) into the score registers
+    //     slots 80-95   PV of the last row block under the multiply-adds that put S(it + 1) c - shift into
+    //                   the score registers (inside this loop they hold the exponent, not the raw score)
     // and returns what maxima(it + 1) would: the caller raises shifts before the next step.  The
     // score MFMAs are single inline-assembly statements here (vector-register results, q from
     // accumulation registers); nothing reads a result sooner than 16 slots after its MFMA, far
