@@ -87,7 +87,9 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     // loop (8 writes, 8 reads and their waits per step: 220 against 236 us per launch at 256 rows, 87
     // against 89-91 us at 64), but each cache line is requested twice; with one row block, where HBM
     // is the bound, it measured 0.6 us slower at 128k keys, so the staged form stays there.
-    constexpr bool kDirectK = NRB == 4;
+    // (Not in the energy pass: without V in the stream the loads are what the step waits for, and at
+    // 64 rows the staged form takes 44.6 against 52.5 us at 128k keys.)
+    constexpr bool kDirectK = NRB == 4 && MODE != kEnergy;
     // With four row blocks a lane needs more than 256 registers, and the compiler then gives EVERY
     // MFMA its result in accumulation registers, which the vector ALU cannot address: each score
     // would cost a v_accvgpr_read (8 cycles per instruction, 32 per step).  The numerators belong
@@ -298,15 +300,17 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     float sv[NRB][8];   // unscaled scores q.k of the current step, slot e = 4G + i (-inf where masked)
     float m8[NRB];      // largest of this lane's 8 unscaled scores of the current step
 
-    auto front = [&](auto tail_c, row_t (&kr)[8], v4i (&ka)[2][kSteps], int it) -> bool {
+    // `ahead`: which later step the K registers are refilled with once they have been consumed (1, or 2
+    // where two K tiles alternate).
+    auto front = [&](auto tail_c, row_t (&kr)[8], v4i (&ka)[2][kSteps], int it, int ahead = 1) -> bool {
         constexpr bool masked = decltype(tail_c)::value;
         if constexpr (!kDirectK) {
             // ---- K tile: registers -> LDS (row-major, padded), next tile requested
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 *reinterpret_cast<row_t *>(stage + trow[e] * kPitch + c * kLaneBytes) = kr[e];
-            if constexpr (!masked) issue_k_full(kr, it + 1);
-            else if (it + 1 < n_iters) issue_k(kr, it + 1);
+            if constexpr (!masked) issue_k_full(kr, it + ahead);
+            else if (it + ahead < n_iters) issue_k(kr, it + ahead);
         }
 
         // S = K Q^T.  The 2 key groups x NRB row blocks are independent accumulation chains; the
@@ -382,8 +386,8 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
             }
         }
         if constexpr (kDirectK) {   // the MFMAs above have read the tile: request the next one
-            if constexpr (!masked) issue_kd_full(ka, it + 1);
-            else if (it + 1 < n_iters) issue_kd(ka, it + 1);
+            if constexpr (!masked) issue_kd_full(ka, it + ahead);
+            else if (it + ahead < n_iters) issue_kd(ka, it + ahead);
         }
 
         // per row block this lane owns 8 keys of one row.  The steady state needs no row maximum,
@@ -651,7 +655,36 @@ __device__ __forceinline__ void process_range(const PartialArgs &a, const Range 
     row_t kr[8], vr[8];
     v4i ka[2][kSteps];
     int it = 0;
-    if constexpr (!kPipelined) {
+    if constexpr (MODE == kEnergy && D == 64) {
+        // K is the only stream, a step is short (no PV) and at d = 64 a wave's tile is 4 KB: with one
+        // tile in flight the launch is bound by latency (256k keys: 52.9 us against 42.9).  Two K tiles
+        // alternate, each refilled with the step after next as soon as it has been consumed.  (At
+        // d = 128, with 8 KB per tile, the second tile costs 1 us at 128k keys and 6 us at 1M.)
+        row_t kr2[8];
+        v4i ka2[2][kSteps];
+        auto issue_any = [&](row_t (&r8)[8], v4i (&a8)[2][kSteps], int i) {
+            if constexpr (kDirectK) issue_kd(a8, i); else issue_k(r8, i);
+        };
+        const int n_steady = n_full > 2 ? (n_full - 2) & ~1 : 0;   // pairs of full tiles whose refills are full tiles too
+        issue_any(kr, ka, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (n_iters > 1) issue_any(kr2, ka2, 1);
+        finish_q();
+        for (; it < n_steady; it += 2) {
+            if (front(std::false_type{}, kr, ka, it, 2)) raise();
+            back(std::false_type{}, std::false_type{}, vr, it);
+            if (front(std::false_type{}, kr2, ka2, it + 1, 2)) raise();
+            back(std::false_type{}, std::false_type{}, vr, it + 1);
+        }
+        for (; it < n_iters; it += 2) {   // last full tiles, ragged tail, causal limits
+            if (front(std::true_type{}, kr, ka, it, 2)) raise();
+            back(std::true_type{}, std::false_type{}, vr, it);
+            if (it + 1 < n_iters) {
+                if (front(std::true_type{}, kr2, ka2, it + 1, 2)) raise();
+                back(std::true_type{}, std::false_type{}, vr, it + 1);
+            }
+        }
+    } else if constexpr (!kPipelined) {
         const int n_steady = n_full > 0 ? n_full - 1 : 0;   // full tiles whose successor is a full tile too
         if (n_steady > 0) {
             if constexpr (kDirectK) issue_kd_full(ka, 0); else issue_k_full(kr, 0);
