@@ -400,13 +400,16 @@ def main():
                           args.graph, args.op)
     if args.workload == "llama128k" and not args.no_extra and args.op == "decode" and not args.keys:
         # the metric is quoted at 128k and at 1M keys; the other configurations of the task (ragged batch,
-        # tree-combine stress), several query tokens and the energy pass ride along, a few steps each
+        # tree-combine stress), several query tokens (64 and 256 rows: the second is the one bound by the
+        # matrix cores), fp32 K/V and the energy pass ride along, a few steps each
         keep = ("value", "unit", "us_per_step", "us_per_step_stats", "pct_of_hbm_peak", "steps", "config", "roofline")
         result["also"] = {}
         for name, op, n_steps in (("million", "decode", max(10, args.steps // 2)),
                                   ("ragged", "decode", max(10, args.steps // 2)),
                                   ("combine", "decode", max(10, args.steps // 2)),
                                   ("llama128k_sq16", "decode", args.steps),
+                                  ("llama128k_sq64", "decode", max(10, args.steps // 2)),
+                                  ("f32_64k", "decode", args.steps),
                                   ("llama128k", "energy", args.steps)):
             torch.cuda.empty_cache()
             m = run_workload(name, n_steps, max(3, args.warmup // 4), False, False, op)

@@ -70,6 +70,8 @@ def test_bench_reports_the_matrix_core_roofline_where_it_binds_and_the_extra_wor
                        capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stderr[-2000:]
     rec = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][0])
-    assert set(rec["also"]) == {"million", "ragged", "combine", "llama128k_sq16", "llama128k:energy"}
+    assert set(rec["also"]) == {"million", "ragged", "combine", "llama128k_sq16", "llama128k_sq64", "f32_64k",
+                                "llama128k:energy"}
     for k, v in rec["also"].items():
-        assert v["roofline"]["bound"] == "hbm" and v["value"] > 0 and v["config"]["workload"] in k
+        assert v["roofline"]["bound"] == ("mfma" if k == "llama128k_sq64" else "hbm")
+        assert v["value"] > 0 and v["config"]["workload"] in k
