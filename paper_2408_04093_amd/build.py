@@ -30,21 +30,23 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-PROBE_SRC = os.path.join(HERE, "..", "bench", "hbm_probe.hip")
-PROBE_BIN = os.path.join(HERE, "..", "bench", "hbm_probe")
+BENCH_DIR = os.path.join(HERE, "..", "bench")
+PROBES = ("hbm_probe", "l2_read_probe")   # stand-alone measurement aids, not part of the library
 
 
 def build_probe(verbose: bool = False) -> str:
-    """The stand-alone HBM read/copy probe (measurement aid, not part of the library)."""
+    """The stand-alone probes under bench/ (HBM read/copy ceiling and counter calibration; reads of
+    L2-resident data by access pattern).  Returns the path of the first."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", PROBE_SRC, "-o", PROBE_BIN]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr)
-    return PROBE_BIN
+    for name in PROBES:
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", os.path.join(BENCH_DIR, name + ".hip"), "-o", os.path.join(BENCH_DIR, name)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return os.path.join(BENCH_DIR, PROBES[0])
 
 
 def build(verbose: bool = False, extra=()) -> str:
