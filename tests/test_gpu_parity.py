@@ -410,6 +410,40 @@ def test_scores_rising_along_the_sequence_move_the_shift_at_every_step(Sq, d):
             check(w, f32_out_tol=2e-4)
 
 
+@pytest.mark.parametrize("Sq,d,P", [(16, 128, 1), (16, 64, 1), (16, 128, 2), (40, 128, 1), (8, 128, 1), (1, 128, 1)])
+def test_scores_rising_inside_one_long_chunk(Sq, d, P):
+    """The same ramp with the chunk count fixed by the caller, so that a workgroup streams 1500 to 3000
+    keys and its steady loop runs for many steps (the library's own choice for so short a sequence is
+    chunks of ~256 keys, which never get there): with four row blocks that loop is the software
+    pipeline whose score registers hold exponents relative to the current shift, and here the shift
+    moves after every one of its steps.  Both directions of the ramp, ragged lengths, against the
+    oracle through ta_decode_partial + ta_tree_combine."""
+    B, Hq, Hkv, N = 2, 8, 2, 3000
+    g = torch.Generator().manual_seed(700 + Sq + d)
+    u = torch.randn(d, generator=g)
+    u /= u.norm()
+    shape_q = (B, Sq, Hq, d) if Sq > 1 else (B, Hq, d)
+    q = (2.0 * u + 0.3 * torch.randn(shape_q, generator=g)).to(torch.bfloat16)
+    ramp = torch.arange(N, dtype=torch.float32) / 128.0
+    K = (3.25 * ramp[:, None] * u[None, :] + 0.5 * torch.randn((B, Hkv, N, d), generator=g)).to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, d), generator=g).to(torch.bfloat16)
+    for Kx in (K, K.flip(2).contiguous()):
+        for vl in (None, torch.tensor([N, 1777], dtype=torch.int32)):
+            qd, Kd, Vd = q.cuda(), Kx.cuda(), V.cuda()
+            vld = None if vl is None else vl.cuda()
+            pm, pl, po = ta.decode_partial(qd, Kd, Vd, 1.0, P, vld)
+            out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+            torch.cuda.synchronize()
+            vln = None if vl is None else vl.numpy()
+            if Sq > 1:
+                ref_out, ref_lse = oracle.decode_causal(q, Kx, V, 1.0, vln)
+            else:
+                ref_out, ref_lse = oracle.decode(q, Kx, V, 1.0, vln)
+            assert np.abs(ref_lse).max() > 100
+            assert row_rel_l2(out.cpu().numpy(), ref_out) <= 2e-4      # scores reach ~150: fp32 resolves 1.5e-5 there
+            assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
+
+
 @pytest.mark.parametrize("Sq,Hq,Hkv,d", [(1, 8, 2, 128), (1, 8, 2, 64), (1, 4, 2, 128), (3, 8, 2, 64), (1, 3, 1, 128)])
 def test_scores_rising_along_the_sequence_fp32_kv(Sq, Hq, Hkv, d):
     """The same ramp with fp32 K/V: on the vector-ALU kernel a lane keeps the running max of ONE of
@@ -998,14 +1032,24 @@ def test_very_large_ragged_batch_falls_back_to_chunks():
 @pytest.mark.parametrize("N", [140, 270, 400, 530, 655, 790, 915, 1045])
 def test_multi_token_four_row_blocks_every_length_of_the_steady_loop(N, d):
     """64 (token, head) rows per kv head: the kernel whose steady steps are a hand-scheduled
-    software pipeline entered through a rotated loop.  With 128 keys per workgroup step these
-    lengths give 0 to 7 full tiles visible to every row, i.e. every number of pipelined steps from
-    none to five, each followed by the masked tail."""
+    software pipeline entered through a rotated loop.  With 128 keys per workgroup step and one
+    chunk per sequence these lengths give 0 to 7 full tiles visible to every row, i.e. every number
+    of pipelined steps from none to five, each followed by the masked tail."""
     w = W.make_multi(1, 16, 4, 1, d, N, torch.bfloat16, seed=5100 + N + d, device="cuda")
     check_multi(w)
     w2 = W.make_multi(2, 8, 16, 2, d, N, torch.bfloat16, seed=5200 + N + d, device="cuda")
     w2.valid_len = torch.tensor([N, N - 37], dtype=torch.int32, device="cuda")
     check_multi(w2)
+    # the library itself cuts so short a sequence into chunks of ~256 keys; one chunk per sequence
+    # is what makes a workgroup walk all of it
+    for x in (w, w2):
+        pm, pl, po = ta.decode_partial(x.q, x.K, x.V, x.scale, 1, x.valid_len)
+        out, lse = ta.tree_combine(pm, pl, po, ta.TA_F32)
+        torch.cuda.synchronize()
+        vl = None if x.valid_len is None else x.valid_len.cpu().numpy()
+        ref_out, ref_lse = oracle.decode_causal(x.q.cpu(), x.K.cpu(), x.V.cpu(), x.scale, vl)
+        assert row_rel_l2(out.cpu().numpy(), ref_out) <= TOL_BF16_F32OUT
+        assert lse_err(lse.cpu().numpy(), ref_lse) <= TOL_LSE
 
 
 @pytest.mark.parametrize("d", [128, 64])
