@@ -162,10 +162,10 @@ ta_status ta_tree_combine(int32_t B, int32_t Hq, int32_t d, int32_t P,
  * chunks into `workspace`, then ta_tree_combine.  When P = 1 (short contexts
  * in a large batch) the single chunk is the result: the streaming kernel
  * normalises and stores out / lse itself and no second kernel is launched.
- * When valid_len is given (a ragged batch; bf16, B <= 2048) the chunks
- * are not fixed-size: all valid keys of the batch are cut into one equal-cost
- * share per compute unit on the device, whatever the mix of lengths, and the
- * combine merges each row's pieces.  The result is the same attention output;
+ * When valid_len is given (a ragged batch, B <= 2048) the chunks are not
+ * fixed-size: all valid keys of the batch are cut into equal-cost shares on
+ * the device, one per workgroup the GPU holds at a time, whatever the mix of
+ * lengths, and the combine merges each row's pieces.  The result is the same attention output;
  * only the (private) workspace layout differs.
  *   workspace        device scratch, 256-byte aligned, at least
  *                    ta_workspace_bytes(p, ta_suggest_chunks(p)) bytes;
