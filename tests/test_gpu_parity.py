@@ -520,6 +520,41 @@ def test_seeded_random_problems_against_the_oracle(seed):
     assert row_rel_l2(out2.cpu().numpy(), ref[0]) <= TOL_BF16_F32OUT
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_problems_fp32_kv(seed):
+    """The same draw for fp32 K/V (vector-ALU kernel: 4, 2 or 1 rows per workgroup depending on how the
+    (token, head) rows of a kv head divide, both head dimensions, chunked and balanced launches), at
+    the fp32 bar: the whole path, the two halves with an explicit chunk count, Algorithm 1 alone and
+    Algorithms 1 + 2."""
+    rng = np.random.default_rng(8000 + seed)
+    d = int(rng.choice([64, 128]))
+    B = int(rng.integers(1, 5))
+    Hkv = int(rng.integers(1, 4))
+    g = int(rng.choice([1, 2, 3, 4, 6, 8, 12]))
+    Sq = int(rng.choice([1, 1, 1, 2, 3, 4]))
+    N = int(rng.choice([1, 7, 63, 64, 65, 500, 1024, 1500, 4097]))
+    scale = float(rng.choice([1.0, -0.7, 0.0, 0.25])) * d ** -0.5
+    if Sq > 1:
+        w = W.make_multi(B, Sq, g * Hkv, Hkv, d, N, torch.float32, seed=8100 + seed, device="cuda", scale=scale)
+    else:
+        w = W.make_qkv(B, g * Hkv, Hkv, d, N, torch.float32, seed=8100 + seed, device="cuda", scale=scale)
+    if rng.random() < 0.5:
+        w.valid_len = torch.from_numpy(rng.integers(0, N + 1, size=B).astype(np.int32)).cuda()
+    vl = None if w.valid_len is None else w.valid_len.cpu().numpy()
+    ref = (oracle.decode_causal if Sq > 1 else oracle.decode)(w.q.cpu(), w.K.cpu(), w.V.cpu(), w.scale, vl)
+    P = int(rng.choice([1, 2, 5, 13]))
+    pm, pl, po = ta.decode_partial(w.q, w.K, w.V, w.scale, P=P, valid_len=w.valid_len)
+    results = [ta.decode(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32), ta.tree_combine(pm, pl, po, ta.TA_F32),
+               ta.decode_two_pass(w.q, w.K, w.V, w.scale, w.valid_len, ta.TA_F32)]
+    lse_e = ta.energy(w.q, w.K, w.scale, w.valid_len)
+    torch.cuda.synchronize()
+    for out, lse in results:
+        assert np.isfinite(out.cpu().numpy()).all()
+        assert row_rel_l2(out.cpu().numpy(), ref[0]) <= TOL_F32
+        assert lse_err(lse.cpu().numpy(), ref[1]) <= TOL_LSE
+    assert lse_err(lse_e.cpu().numpy(), ref[1]) <= TOL_LSE and torch.equal(lse_e, results[2][1])
+
+
 # ------------------------------------------------------------------ full-size configs, bench launch shape
 def test_config1_llama_128k_full():
     w = W.llama128k(device="cuda")
