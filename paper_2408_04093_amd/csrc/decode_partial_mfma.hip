@@ -31,8 +31,8 @@
 //       a 16-bit interleave of register pairs puts them in B layout.  8 MFMAs
 //       (one per j) cover all 128 columns: acc_j[i] = O[head 4r+i][col 8c+j].
 //   P is split into bf16 hi + bf16 lo (two MFMAs per j) so that the
-//       probabilities keep 16 significant bits; rounding P to one bf16 would
-//       cost ~1e-3 relative error in the output.
+//       probabilities keep 16 significant bits; rounding P to one bf16 costs
+//       1.6e-3 relative error in the output (measured; 2.5e-6 with hi + lo).
 // The contraction order of keys inside a tile is a fixed permutation
 // (kappa below) applied to P and V alike.
 #include <type_traits>
