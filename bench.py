@@ -30,6 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 on the matrix cores, published
 LLC_BYTES = 256 << 20      # Infinity Cache
 SETTLE_MS = 20             # untimed steps before the W warm-up steps (clock settling)
 IDLE_MS_AFTER_SETUP = 2000 # idle time between building the inputs and the first step (see run_workload)
+BALLAST_GIB = 16           # device memory taken (untouched) before any input is allocated, held to the end (see main)
 KERNEL_SOURCES = ["decode_partial_mfma.hip", "mfma_tile.hpp", "chunking.hpp", "balanced_index.hpp", "balanced_walk.hpp",
                   "wave_ops.hpp", "ta_internal.hpp", "ta_api.cpp"]
 
@@ -395,6 +396,13 @@ def main():
     ta.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    # The first device memory a process obtains shortly after another process has released tens of GB (a test
+    # suite, a previous benchmark) comes in smaller physical fragments: the same kernel ran 3-9 % slower on
+    # buffers allocated then, for as long as those buffers lived, while buffers allocated later in the same
+    # process, or by a process started 20 s later, were normal (address translation misses, not the kernel:
+    # same virtual addresses, same code).  So that the inputs do not depend on what ran on the box before,
+    # the process first takes a block of memory that it never touches and keeps it.
+    ballast = torch.empty(BALLAST_GIB << 30, dtype=torch.uint8, device="cuda")
 
     result = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline and args.op == "decode",
                           args.graph, args.op)
@@ -420,6 +428,8 @@ def main():
         if sc is not None:
             sc["frac_of_it"] = round(result["roofline"]["achieved"] / sc["value"], 4)
         result["roofline"]["stream_ceiling"] = sc
+    result["ballast_gib_held"] = BALLAST_GIB
+    del ballast
     print(json.dumps(result), flush=True)
 
 

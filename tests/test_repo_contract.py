@@ -44,7 +44,7 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     rec = json.loads(lines[0])
     for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better",
               "scaling", "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline",
-              "idle_ms_after_setup", "settle_ms_before_warmup"):
+              "idle_ms_after_setup", "settle_ms_before_warmup", "ballast_gib_held"):
         assert k in rec, k
     assert rec["n_gpus"] == 1 and rec["steps"] == 5 and rec["unit"] == "GB/s" and rec["data"] == "synthetic"
     assert rec["config"]["workload"] == "llama128k" and rec["vs_baseline"] is None
