@@ -566,7 +566,7 @@ def test_config1_llama_128k_full():
 def test_config1_llama_128k_other_seeds(seed_offset):
     """The headline shape on three more draws: the bf16-output rel-L2 of this 4096-element tensor sits
     close to the 2e-3 bar by construction (it is the rounding to 8 bits itself), so the margin is
-    measured on several seeds, not one.  The figures are printed (-s) and recorded in the design doc."""
+    measured on several seeds, not one.  The figures are printed (-s)."""
     w = W.llama128k(device="cuda", seed_offset=seed_offset)
     ref_out, ref_lse = oracle_of(w)
     out, lse = check(w, ref=(ref_out, ref_lse))
