@@ -109,3 +109,14 @@ def test_whole_tensor_bar_applies_from_2048_elements(ref):
     assert ref.size >= 2048 and TOL_BF16_F32OUT < 1e-3
     with pytest.raises(AssertionError):
         check_bf16_output(rne(f32), f32, ref)
+
+
+def test_an_all_zero_reference_demands_exact_zeros():
+    # every sequence of the batch empty: the whole result is zero, the relative error 0 / 0
+    ref = np.zeros((2, 64, 64))
+    zeros = np.zeros((2, 64, 64), np.float32)
+    check_bf16_output(zeros.copy(), zeros, ref)
+    bad = zeros.copy()
+    bad[1, 3, 5] = 1e-30
+    with pytest.raises(AssertionError):
+        check_bf16_output(rne(bad), bad, ref)
